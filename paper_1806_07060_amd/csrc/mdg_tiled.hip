@@ -1,0 +1,343 @@
+// Tiled matrix-core kernel: the specialised member of the family (Section 2.3
+// of the paper: a tiled kernel that relies on data reuse in local memory).
+// Unlike the "indirect" kernel described there it needs no pad/transpose helper
+// passes: transposes are absorbed by the global->LDS load path and ragged
+// edges by guarded loads on the border tiles only.
+//
+// Work decomposition (column-major C, M contiguous)
+//   work-group : BM x BN tile of C, K range [k_begin, k_end) (one slice when split_k > 1)
+//   wave       : WTM x WTN sub-tile, WTM = BM / WGM, WTN = BN / WGN, as FM x FN blocks of 32 x 32
+//   MFMA       : v_mfma_f32_32x32x2_f32 (true fp32 operands, fp32 accumulate).
+//                The ROW operand of the instruction is fed from op(B) (index n), the
+//                COLUMN operand from op(A) (index m), i.e. each block holds a 32 x 32
+//                piece of C^T: the lane index then runs along m, the contiguous index
+//                of C, and stores are full cache lines.
+//   lane (h, p), h = lane / 32, p = lane % 32
+//     operand registers: k = kk + h;  m_local = FM * p + b  (b = block),  n_local = FN * p + c
+//       -> one ds_read of FM (resp. FN) consecutive floats feeds FM (FN) blocks
+//     accumulator register r of block (c, b):  n_local = FN * (8 * (r / 4) + 4 * h + r % 4) + c,
+//                                              m_local = FM * p + b
+//       -> for fixed (c, r) the FM values of a lane are consecutive in m: one vector store.
+//
+// LDS: two stages of As[BK][BM + 4] and Bs[BK][BN + 4] (k-major rows, the
+// non-contracted index contiguous).  Global loads are float4 along whichever
+// index is contiguous in memory; operands stored with k contiguous are
+// transposed on their way into LDS (four 4-byte writes; the +4 padding spreads
+// them over the banks).  One barrier per K step: loads for step t+1 are issued
+// before the MFMAs of step t and written to the other stage after them.
+#include "mdg_internal.h"
+#include "mdg_variant_list.h"
+
+namespace mdg {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+struct TiledParams {
+  const float* A;
+  const float* B;
+  float* C;
+  float* ws;
+  int64_t lda, ldb, ldc;
+  int M, N, K;
+  int tiles_m, tiles_n;
+  int split_k, k_per_split;
+  float alpha, beta;
+  int a_vec, b_vec;  // 1 if float4 global loads of that operand are aligned
+};
+
+constexpr int kPad = 4;
+constexpr int kGroupM = 8;  // tiles per group along M in the tile ordering
+
+// Loads one BMN x BK operand tile into registers (float4 slots).
+//   KMAJOR = stored with k contiguous:  X[k + mn * ld]   else   X[mn + k * ld]
+// `fast` (work-group uniform) = whole tile in range and vector loads aligned.
+template <int BMN, int BK, int NT, bool KMAJOR>
+struct OperandLoader {
+  static constexpr int kSlots = BMN * BK / 4 / NT;
+  static_assert(BMN * BK % (4 * NT) == 0, "tile must split evenly into float4 slots");
+
+  __device__ __forceinline__ static void coords(int slot, int tid, int& mn, int& k) {
+    int v = tid + slot * NT;
+    if (KMAJOR) {
+      k = (v % (BK / 4)) * 4;
+      mn = v / (BK / 4);
+    } else {
+      mn = (v % (BMN / 4)) * 4;
+      k = v / (BMN / 4);
+    }
+  }
+
+  __device__ __forceinline__ static void load(floatx4 (&r)[kSlots], const float* __restrict__ X, int64_t ld, int mn0,
+                                              int k0, int mn_lim, int k_lim, bool fast, int tid) {
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) {
+      int mn, k;
+      coords(s, tid, mn, k);
+      mn += mn0;
+      k += k0;
+      if (fast) {
+        const float* src = KMAJOR ? X + (int64_t)k + (int64_t)mn * ld : X + (int64_t)mn + (int64_t)k * ld;
+        r[s] = *reinterpret_cast<const floatx4*>(src);
+      } else {
+        floatx4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int mm = KMAJOR ? mn : mn + e;
+          int kk = KMAJOR ? k + e : k;
+          float x = 0.f;
+          if (mm < mn_lim && kk < k_lim) x = KMAJOR ? X[(int64_t)kk + (int64_t)mm * ld] : X[(int64_t)mm + (int64_t)kk * ld];
+          v[e] = x;
+        }
+        r[s] = v;
+      }
+    }
+  }
+
+  // registers -> LDS stage S[BK][BMN + kPad]
+  __device__ __forceinline__ static void store(const floatx4 (&r)[kSlots], float* S, int tid) {
+    constexpr int LD = BMN + kPad;
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) {
+      int mn, k;
+      coords(s, tid, mn, k);
+      if (KMAJOR) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) S[(k + e) * LD + mn] = r[s][e];
+      } else {
+        *reinterpret_cast<floatx4*>(&S[k * LD + mn]) = r[s];
+      }
+    }
+  }
+};
+
+template <int F>
+struct Frag {
+  float v[F];
+};
+
+template <int F>
+__device__ __forceinline__ void lds_read_frag(float (&dst)[F], const float* src) {
+  if constexpr (F == 4) {
+    floatx4 t = *reinterpret_cast<const floatx4*>(src);
+    dst[0] = t[0], dst[1] = t[1], dst[2] = t[2], dst[3] = t[3];
+  } else if constexpr (F == 2) {
+    floatx2 t = *reinterpret_cast<const floatx2*>(src);
+    dst[0] = t[0], dst[1] = t[1];
+  } else {
+    dst[0] = *src;
+  }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool TA, bool TB>
+__global__ __launch_bounds__(64 * WGM * WGN) void tiled_kernel(TiledParams p) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  static_assert(FM == 1 || FM == 2 || FM == 4, "wave tile rows must be 32, 64 or 128");
+  static_assert(FN == 1 || FN == 2 || FN == 4, "wave tile columns must be 32, 64 or 128");
+  constexpr int LDA_S = BM + kPad, LDB_S = BN + kPad;
+  constexpr int A_STAGE = BK * LDA_S, B_STAGE = BK * LDB_S;
+  // A is k-contiguous when transposed; B is k-contiguous when not transposed.
+  using LoadA = OperandLoader<BM, BK, NT, TA>;
+  using LoadB = OperandLoader<BN, BK, NT, !TB>;
+
+  __shared__ __attribute__((aligned(16))) float lds[2 * (A_STAGE + B_STAGE)];
+  float* As = lds;
+  float* Bs = lds + 2 * A_STAGE;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int h = lane >> 5, pl = lane & 31;
+  const int wm = wave % WGM, wn = wave / WGM;
+
+  // ---- which tile: undo the round-robin of work-groups over the 8 XCDs so that each
+  // XCD (own L2) works on a compact block of neighbouring tiles, then walk the tiles in
+  // groups of kGroupM rows.
+  const int tiles = p.tiles_m * p.tiles_n;
+  int bid = blockIdx.x;
+  const int split = bid / tiles;
+  bid -= split * tiles;
+  {
+    const int per = (tiles + 7) >> 3, rem = tiles & 7, xcd = bid & 7, loc = bid >> 3;
+    bid = (rem == 0 || xcd < rem) ? xcd * per + loc : rem * per + (xcd - rem) * (per - 1) + loc;
+  }
+  const int group_sz = kGroupM * p.tiles_n;
+  const int group = bid / group_sz;
+  const int first_m = group * kGroupM;
+  const int gm = min(p.tiles_m - first_m, kGroupM);
+  const int in_group = bid - group * group_sz;
+  const int tile_m = first_m + in_group % gm;
+  const int tile_n = in_group / gm;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int k_begin = split * p.k_per_split;
+  const int k_end = min(p.K, k_begin + p.k_per_split);
+  const int n_steps = (k_end - k_begin + BK - 1) / BK;
+
+  const bool a_full = p.a_vec && (m0 + BM <= p.M);
+  const bool b_full = p.b_vec && (n0 + BN <= p.N);
+
+  floatx16 acc[FN][FM];
+#pragma unroll
+  for (int c = 0; c < FN; ++c)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[c][b][r] = 0.f;
+
+  floatx4 ra[LoadA::kSlots], rb[LoadB::kSlots];
+
+  if (n_steps > 0) {
+    const bool kfull = (k_begin + BK <= k_end);
+    LoadA::load(ra, p.A, p.lda, m0, k_begin, p.M, k_end, a_full && kfull, tid);
+    LoadB::load(rb, p.B, p.ldb, n0, k_begin, p.N, k_end, b_full && kfull, tid);
+    LoadA::store(ra, As, tid);
+    LoadB::store(rb, Bs, tid);
+  }
+  __syncthreads();
+
+  const float* a_rd = As + h * LDA_S + wm * WTM + FM * pl;
+  const float* b_rd = Bs + h * LDB_S + wn * WTN + FN * pl;
+
+  for (int t = 0; t < n_steps; ++t) {
+    const int buf = t & 1;
+    const bool more = (t + 1 < n_steps);
+    if (more) {
+      const int k0 = k_begin + (t + 1) * BK;
+      const bool kfull = (k0 + BK <= k_end);
+      LoadA::load(ra, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, tid);
+      LoadB::load(rb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, tid);
+    }
+    const float* a_s = a_rd + buf * A_STAGE;
+    const float* b_s = b_rd + buf * B_STAGE;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float af[FM], bf[FN];
+      lds_read_frag<FM>(af, a_s + kk * LDA_S);
+      lds_read_frag<FN>(bf, b_s + kk * LDB_S);
+#pragma unroll
+      for (int c = 0; c < FN; ++c)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+          acc[c][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[c], af[b], acc[c][b], 0, 0, 0);
+    }
+    if (more) {
+      LoadA::store(ra, As + (buf ^ 1) * A_STAGE, tid);
+      LoadB::store(rb, Bs + (buf ^ 1) * B_STAGE, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue
+  const int m_base = m0 + wm * WTM + FM * pl;
+  const int n_wave = n0 + wn * WTN;
+  if (p.split_k > 1) {
+    // raw partial sums into slice `split` of the workspace (tight column-major M x N)
+    float* W = p.ws + (int64_t)split * p.M * p.N;
+    const bool vec = (FM > 1) && ((p.M & 3) == 0) && (m_base + FM <= p.M);
+#pragma unroll
+    for (int c = 0; c < FN; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
+        if (n >= p.N) continue;
+        float* dst = W + (int64_t)m_base + (int64_t)n * p.M;
+        if (vec) {
+          if constexpr (FM == 4) {
+            floatx4 o = {acc[c][0][r], acc[c][1][r], acc[c][2][r], acc[c][3][r]};
+            *reinterpret_cast<floatx4*>(dst) = o;
+          } else if constexpr (FM == 2) {
+            floatx2 o = {acc[c][0][r], acc[c][1][r]};
+            *reinterpret_cast<floatx2*>(dst) = o;
+          }
+        } else {
+#pragma unroll
+          for (int b = 0; b < FM; ++b)
+            if (m_base + b < p.M) dst[b] = acc[c][b][r];
+        }
+      }
+    return;
+  }
+
+  const bool c_al = ((p.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
+  const bool vec = (FM > 1) && c_al && (m_base + FM <= p.M);
+  const float alpha = p.alpha, beta = p.beta;
+#pragma unroll
+  for (int c = 0; c < FN; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
+      if (n >= p.N) continue;
+      float* dst = p.C + (int64_t)m_base + (int64_t)n * p.ldc;
+      if (vec) {
+        if constexpr (FM == 4) {
+          floatx4 o = {alpha * acc[c][0][r], alpha * acc[c][1][r], alpha * acc[c][2][r], alpha * acc[c][3][r]};
+          if (beta != 0.f) {
+            floatx4 old = *reinterpret_cast<const floatx4*>(dst);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = fmaf(beta, old[e], o[e]);
+          }
+          *reinterpret_cast<floatx4*>(dst) = o;
+        } else if constexpr (FM == 2) {
+          floatx2 o = {alpha * acc[c][0][r], alpha * acc[c][1][r]};
+          if (beta != 0.f) {
+            floatx2 old = *reinterpret_cast<const floatx2*>(dst);
+            o[0] = fmaf(beta, old[0], o[0]);
+            o[1] = fmaf(beta, old[1], o[1]);
+          }
+          *reinterpret_cast<floatx2*>(dst) = o;
+        }
+      } else {
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+          if (m_base + b < p.M) {
+            float o = alpha * acc[c][b][r];
+            if (beta != 0.f) o = fmaf(beta, dst[b], o);
+            dst[b] = o;
+          }
+      }
+    }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN>
+static int launch_cfg(int split_k, const GemmArgs& g) {
+  TiledParams p;
+  p.A = g.A, p.B = g.B, p.C = g.C, p.ws = g.ws;
+  p.lda = g.lda, p.ldb = g.ldb, p.ldc = g.ldc;
+  p.M = (int)g.M, p.N = (int)g.N, p.K = (int)g.K;
+  const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  if (tiles_m * tiles_n * split_k > 0x7fffffffLL) return MDG_ERR_LAUNCH;
+  p.tiles_m = (int)tiles_m, p.tiles_n = (int)tiles_n;
+  p.split_k = split_k;
+  const int64_t k_steps = (g.K + BK - 1) / BK;
+  p.k_per_split = (int)(((k_steps + split_k - 1) / split_k) * BK);
+  p.alpha = g.alpha, p.beta = g.beta;
+  p.a_vec = ((g.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0);
+  p.b_vec = ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
+  dim3 grid((unsigned)(tiles_m * tiles_n * split_k)), block(64 * WGM * WGN);
+  if (g.tA) {
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, true, true><<<grid, block, 0, g.stream>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, true, false><<<grid, block, 0, g.stream>>>(p);
+  } else {
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, false, true><<<grid, block, 0, g.stream>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, false, false><<<grid, block, 0, g.stream>>>(p);
+  }
+  int st = check_launch();
+  if (st != MDG_OK || split_k == 1) return st;
+  return launch_splitk_reduce(split_k, g);
+}
+
+int launch_tiled(int cfg, int split_k, const GemmArgs& g) {
+  switch (cfg) {
+#define X(c, BM, BN, BK, WGM, WGN) \
+  case c:                          \
+    return launch_cfg<BM, BN, BK, WGM, WGN>(split_k, g);
+    MDG_TILED_CONFIGS(X)
+#undef X
+  }
+  return MDG_ERR_BAD_VARIANT;
+}
+
+}  // namespace mdg

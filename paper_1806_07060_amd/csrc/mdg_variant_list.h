@@ -1,0 +1,87 @@
+// The tuning space: one line per compiled kernel configuration, one table of variants.
+// Single source of truth for the kernels' template instantiations, the variant
+// table (mdg_variant_info), legality and the selector's class ids.
+//
+// The paper's library exposes thousands of parameter points per kernel
+// (Section 4.1, tuning-size table); this family is deliberately small, built
+// for wave64 matrix cores and 160 KB of LDS rather than for the OpenCL devices
+// studied there.
+#pragma once
+
+// Direct (generic) kernel: 16 x 16 threads, each computing TM x TN elements of C.
+//   X(cfg, TM, TN, LDS)     tile = 16*TM x 16*TN, K step 16 when staged through LDS
+#define MDG_DIRECT_CONFIGS(X) \
+  X(0, 4, 4, 1)               \
+  X(1, 1, 1, 0)               \
+  X(2, 2, 2, 0)               \
+  X(3, 2, 2, 1)               \
+  X(4, 8, 4, 1)               \
+  X(5, 4, 1, 0)               \
+  X(6, 1, 4, 0)
+
+// Tiled matrix-core kernel: work-group tile BM x BN x BK, WGM x WGN waves.
+//   X(cfg, BM, BN, BK, WGM, WGN)
+#define MDG_TILED_CONFIGS(X)   \
+  X(0, 256, 256, 16, 2, 2)     \
+  X(1, 256, 256, 16, 2, 4)     \
+  X(2, 256, 128, 16, 2, 2)     \
+  X(3, 128, 256, 16, 2, 2)     \
+  X(4, 128, 128, 16, 2, 2)     \
+  X(5, 128, 128, 32, 2, 2)     \
+  X(6, 128, 64, 16, 2, 2)      \
+  X(7, 64, 128, 16, 2, 2)      \
+  X(8, 64, 64, 16, 2, 2)       \
+  X(9, 64, 64, 32, 2, 2)       \
+  X(10, 32, 32, 32, 1, 1)      \
+  X(11, 256, 256, 32, 2, 4)
+
+// Skinny-N kernel: streams A once; NB columns of C are held per thread.
+//   X(cfg, NB)
+#define MDG_SKINNY_CONFIGS(X) \
+  X(0, 1)                     \
+  X(1, 4)                     \
+  X(2, 8)                     \
+  X(3, 16)
+
+// The variants: (family, cfg, split_k).  Order defines the public variant ids;
+// id 0 must be legal for every input (the universal fallback).
+//   V(family, cfg, split_k)
+#define MDG_VARIANTS(V) \
+  V(DIRECT, 0, 1)       \
+  V(DIRECT, 1, 1)       \
+  V(DIRECT, 2, 1)       \
+  V(DIRECT, 3, 1)       \
+  V(DIRECT, 4, 1)       \
+  V(DIRECT, 5, 1)       \
+  V(DIRECT, 6, 1)       \
+  V(TILED, 0, 1)        \
+  V(TILED, 1, 1)        \
+  V(TILED, 2, 1)        \
+  V(TILED, 3, 1)        \
+  V(TILED, 4, 1)        \
+  V(TILED, 5, 1)        \
+  V(TILED, 6, 1)        \
+  V(TILED, 7, 1)        \
+  V(TILED, 8, 1)        \
+  V(TILED, 9, 1)        \
+  V(TILED, 10, 1)       \
+  V(TILED, 11, 1)       \
+  V(TILED, 2, 2)        \
+  V(TILED, 4, 2)        \
+  V(TILED, 4, 4)        \
+  V(TILED, 4, 8)        \
+  V(TILED, 8, 2)        \
+  V(TILED, 8, 4)        \
+  V(TILED, 8, 8)        \
+  V(TILED, 8, 16)       \
+  V(TILED, 10, 4)       \
+  V(TILED, 10, 16)      \
+  V(TILED, 10, 64)      \
+  V(SKINNY, 0, 1)       \
+  V(SKINNY, 1, 1)       \
+  V(SKINNY, 2, 1)       \
+  V(SKINNY, 3, 1)       \
+  V(SKINNY, 0, 8)       \
+  V(SKINNY, 1, 8)       \
+  V(SKINNY, 2, 8)       \
+  V(SKINNY, 3, 8)

@@ -1,0 +1,196 @@
+"""GPU parity: every kernel variant, through the C ABI, element by element against the CPU oracle.
+
+Bar: |C - C_ref| <= 1e-6*K*max|a|*max|b| + 1e-6*|beta*C0| for floating-point data, bit-exact for
+small-integer data (every partial sum is then exactly representable in fp32 whatever the summation order).
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_1806_07060_amd import binding as mdg
+from paper_1806_07060_amd import workloads as wl
+from paper_1806_07060_amd.workloads import GemmCase, NO_TRANS as NT, TRANS as TR, COL_MAJOR as CM, ROW_MAJOR as RM
+
+pytestmark = pytest.mark.gpu
+
+TT = list(itertools.product((NT, TR), (NT, TR)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _workspace():
+    from tests import gpu_util as gu
+    gu.ensure_workspace()
+    yield
+
+
+def _gu():
+    from tests import gpu_util as gu
+    return gu
+
+
+def test_config0_every_legal_variant_and_the_selector():
+    gu = _gu()
+    case = wl.config0()[0]
+    st, got, A, B, C0 = gu.run_case(case)
+    assert st == 0
+    ref = gu.oracle_result(case, A, B, C0)
+    gu.check_against_oracle(case, got, A, B, C0, ref=ref)
+    legal = gu.legal_variants(case)
+    assert 0 in legal and len(legal) >= 20
+    for v in legal:
+        st, got, *_ = gu.run_case(case, variant=v)
+        assert st == 0, (v, mdg.mdg_status_string(st))
+        gu.check_against_oracle(case, got, A, B, C0, ref=ref)
+
+
+# shapes that span several tiles of every configuration and leave ragged tails in M, N and K
+RAGGED = [(150, 77, 260), (257, 129, 65), (5, 300, 17), (300, 3, 1000), (33, 4, 2049), (515, 260, 40), (1, 1, 1),
+          (64, 64, 64), (256, 256, 48), (130, 2, 515)]
+
+
+@pytest.mark.parametrize("M,N,K", RAGGED)
+def test_all_variants_all_transposes_ragged_shapes(M, N, K):
+    gu = _gu()
+    for i, (tA, tB) in enumerate(TT):
+        # alternate tight / padded (odd, so nothing is 16-byte aligned) leading dimensions and alpha/beta mixes
+        pad = (0, 0, 0) if i % 2 == 0 else (3, 1, 5)
+        alpha, beta = [(1.0, 0.0), (0.75, 0.5), (-1.5, 1.0), (2.0, -0.25)][i]
+        base = GemmCase(M, N, K, tA, tB, alpha, beta, seed=wl.case_seed(10, 1000 * i + M + N + K),
+                        name=f"ragged/{M}x{N}x{K}/{tA}{tB}").resolved()
+        case = GemmCase(**{**base.__dict__, "lda": base.lda + pad[0], "ldb": base.ldb + pad[1], "ldc": base.ldc + pad[2]})
+        A, B, C0 = wl.make_operands(case)
+        ref = gu.oracle_result(case, A, B, C0)
+        for v in gu.legal_variants(case):
+            st, got, *_ = gu.run_case(case, variant=v)
+            assert st == 0, (v, mdg.mdg_status_string(st))
+            try:
+                gu.check_against_oracle(case, got, A, B, C0, ref=ref)
+            except AssertionError as e:
+                raise AssertionError(f"variant {v} {mdg.mdg_variant_info(v)['name']}: {e}") from None
+
+
+@pytest.mark.parametrize("tA,tB", TT)
+def test_small_integer_data_is_bit_exact_for_every_variant(tA, tB):
+    gu = _gu()
+    case = GemmCase(200, 100, 300, tA, tB, 2.0, -1.0, dist="smallint", c0="smallint", ldc=203,
+                    seed=wl.case_seed(11, tA * 10 + tB), name=f"smallint/{tA}{tB}")
+    A, B, C0 = wl.make_operands(case)
+    ref = gu.oracle_result(case, A, B, C0)
+    for v in gu.legal_variants(case):
+        st, got, *_ = gu.run_case(case, variant=v)
+        assert st == 0
+        try:
+            gu.check_against_oracle(case, got, A, B, C0, exact=True, ref=ref)
+        except AssertionError as e:
+            raise AssertionError(f"variant {v} {mdg.mdg_variant_info(v)['name']}: {e}") from None
+
+
+def _variant_named(prefix):
+    for d in mdg.variants():
+        if d["name"].startswith(prefix):
+            return d["id"]
+    raise KeyError(prefix)
+
+
+@pytest.mark.parametrize("prefix", ["direct_64x64", "direct_16x16", "tiled_128x128x16_w2x2_sk1", "tiled_32x32x32_w1x1_sk1",
+                                    "tiled_32x32x32_w1x1_sk4", "skinny_nb4_sk1"])
+def test_brute_force_tiny_shapes(prefix):
+    # every combination of tiny sizes, all transposes, tight and padded leading dimensions
+    gu = _gu()
+    v = _variant_named(prefix)
+    dims = (1, 2, 3, 5, 8, 16, 17)
+    rng = np.random.default_rng(12)
+    n = 0
+    for M, N, K in itertools.product(dims, dims, dims):
+        tA, tB = TT[n % 4]
+        pad = int(rng.integers(0, 4))
+        base = GemmCase(M, N, K, tA, tB, 1.25, 0.5 if n % 3 else 0.0, dist="smallint", c0="smallint",
+                        seed=wl.case_seed(12, n), name=f"tiny/{M}x{N}x{K}").resolved()
+        case = GemmCase(**{**base.__dict__, "lda": base.lda + pad, "ldb": base.ldb + pad, "ldc": base.ldc + pad})
+        n += 1
+        if v not in gu.legal_variants(case):
+            continue
+        st, got, A, B, C0 = gu.run_case(case, variant=v)
+        assert st == 0
+        gu.check_against_oracle(case, got, A, B, C0, exact=True)
+
+
+@pytest.mark.parametrize("layout", [CM, RM])
+def test_special_scalars_degenerate_sizes_and_layouts(layout):
+    gu = _gu()
+    # beta = 0 with NaN in C: not read.  Through the selector and through a tiled and a direct variant.
+    for variant in (None, 0, _variant_named("tiled_64x64x16_w2x2_sk1"), _variant_named("tiled_64x64x16_w2x2_sk4")):
+        case = GemmCase(70, 90, 50, TR, NT, 1.0, 0.0, layout=layout, c0="nan", seed=5, name="beta0-nanC")
+        st, got, A, B, C0 = gu.run_case(case, variant=variant)
+        assert st == 0
+        gu.check_against_oracle(case, got, A, B, C0)
+    # alpha = 0 with NaN in A and B: not read; C = beta*C0
+    case = GemmCase(70, 90, 50, NT, TR, 0.0, 0.5, layout=layout, dist="nan", seed=6, name="alpha0-nanAB")
+    st, got, A, B, C0 = gu.run_case(case)
+    assert st == 0
+    gu.check_against_oracle(case, got, A, B, C0, exact=True)
+    case = GemmCase(70, 90, 50, NT, TR, 0.0, 0.0, layout=layout, dist="nan", c0="nan", seed=6, name="alpha0-beta0")
+    st, got, A, B, C0 = gu.run_case(case)
+    gu.check_against_oracle(case, got, A, B, C0, exact=True)
+    # K = 0, and beta = 1 (no scaling pass at all)
+    for beta in (0.5, 1.0, 0.0):
+        case = GemmCase(33, 21, 0, NT, NT, 1.0, beta, layout=layout, ldc=40, seed=7, name=f"K0-beta{beta}")
+        st, got, A, B, C0 = gu.run_case(case)
+        assert st == 0
+        gu.check_against_oracle(case, got, A, B, C0, exact=True)
+    # M = 0 / N = 0: success, nothing written
+    for M, N in ((0, 5), (5, 0)):
+        case = GemmCase(M, N, 4, layout=layout, beta=0.5, seed=8, name="empty")
+        st, got, A, B, C0 = gu.run_case(case)
+        assert st == 0 and np.array_equal(got, C0, equal_nan=True)
+    # a row-major problem with both transposes and padded leading dimensions
+    case = GemmCase(130, 75, 310, TR, TR, 1.5, -0.5, layout=layout, lda=133, ldb=312, ldc=79, seed=9, name="TT-padded")
+    for variant in [None] + gu.legal_variants(case)[::5]:
+        st, got, A, B, C0 = gu.run_case(case, variant=variant)
+        assert st == 0
+        gu.check_against_oracle(case, got, A, B, C0)
+
+
+def test_forced_variant_errors():
+    gu = _gu()
+    torch = gu.torch_mod()
+    case = GemmCase(64, 64, 64, seed=1)
+    skinny = _variant_named("skinny_nb1_sk1")
+    st, *_ = gu.run_case(case, variant=skinny)
+    assert st == mdg.ERR_ILLEGAL_VARIANT
+    assert gu.run_case(case, variant=10 ** 6)[0] == mdg.ERR_BAD_VARIANT
+    # without a workspace split-K variants are refused when forced, and replaced by variant 0 in mdg_sgemm
+    sk = _variant_named("tiled_64x64x16_w2x2_sk4")
+    assert mdg.mdg_set_workspace(0, 0) == 0
+    try:
+        assert gu.run_case(case, variant=sk)[0] == mdg.ERR_WORKSPACE
+        assert mdg.mdg_variant_legal(sk, 0, 0, 64, 64, 64, 64, 64, 64) == 0
+        st, got, A, B, C0 = gu.run_case(case)
+        assert st == 0
+        gu.check_against_oracle(case, got, A, B, C0)
+    finally:
+        ws = gu._WS["t"]
+        assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0
+    t = torch.empty(1024, dtype=torch.float32, device="cuda")
+    assert mdg.mdg_set_workspace(t.data_ptr() + 4, 1024) != 0  # misaligned workspace refused
+
+
+def test_non_default_stream_and_repeatability():
+    gu = _gu()
+    torch = gu.torch_mod()
+    case = GemmCase(300, 200, 700, NT, TR, 1.0, 0.5, seed=13).resolved()
+    A, B, C0 = wl.make_operands(case)
+    s = torch.cuda.Stream()
+    outs = []
+    for rep in range(2):
+        dA, dB, dC = (torch.from_numpy(x).cuda() for x in (A, B, C0))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            st = mdg.mdg_sgemm(case.layout, case.transA, case.transB, case.M, case.N, case.K, case.alpha, dA.data_ptr(),
+                               case.lda, dB.data_ptr(), case.ldb, case.beta, dC.data_ptr(), case.ldc, s.cuda_stream)
+        assert st == 0
+        s.synchronize()
+        outs.append(dC.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])  # deterministic: no atomics anywhere
+    gu.check_against_oracle(case, outs[0], A, B, C0)

@@ -1,0 +1,111 @@
+"""Host-side checks of the C-ABI library that need no GPU: exports, variant table, validation, legality, selection."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1806_07060_amd import binding as mdg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mdg_sgemm.h")).read()
+    declared = set(re.findall(r"\b(mdg_[a-z_]+)\s*\(", header))
+    assert declared == set(mdg.EXPORTS)
+    L = ctypes.CDLL(mdg.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_variant_table_is_consistent():
+    vs = mdg.variants()
+    assert len(vs) == mdg.mdg_variant_count() >= 20
+    assert len({v["name"] for v in vs}) == len(vs)
+    assert vs[0]["family"] == mdg.FAMILY_DIRECT and vs[0]["split_k"] == 1
+    fams = {v["family"] for v in vs}
+    assert fams == {mdg.FAMILY_DIRECT, mdg.FAMILY_TILED, mdg.FAMILY_SKINNY}
+    for v in vs:
+        assert v["id"] == vs.index(v)
+        assert v["threads"] in (64, 128, 256, 512) and v["split_k"] >= 1
+        if v["family"] == mdg.FAMILY_TILED:
+            assert v["tile_m"] % v["sub_m"] == 0 and v["sub_m"] in (32, 64, 128)
+            assert (v["tile_m"] // v["sub_m"]) * (v["tile_n"] // v["sub_n"]) * 64 == v["threads"]
+    with pytest.raises(ValueError):
+        mdg.mdg_variant_info(len(vs))
+
+
+def test_argument_validation_reports_first_bad_argument():
+    ok = dict(layout=102, transA=111, transB=111, M=4, N=4, K=4, alpha=1.0, A=256, lda=4, B=256, ldb=4, beta=0.0,
+              C=256, ldc=4)
+
+    def call(**kw):
+        d = dict(ok)
+        d.update(kw)
+        return mdg.mdg_sgemm(**d)
+
+    assert call(layout=0) == -1
+    assert call(transA=110) == -2
+    assert call(transB=0) == -3
+    assert call(M=-1) == -4
+    assert call(N=-2) == -5
+    assert call(K=-3) == -6
+    assert call(M=2 ** 31) == -4
+    assert call(A=0) == -8
+    assert call(lda=3) == -9
+    assert call(B=0) == -10
+    assert call(ldb=3) == -11
+    assert call(C=0) == -13
+    assert call(ldc=3) == -14
+    assert call(transA=112, M=8, K=2, lda=1, ldc=8) == -9
+    assert call(layout=101, M=2, N=8, K=4, ldb=7, ldc=8) == -11
+    assert call(layout=101, M=2, N=8, K=4, ldb=8, ldc=7) == -14
+    # nothing to do: returns before touching the GPU
+    assert call(M=0, lda=1, ldc=1) == 0
+    assert call(N=0) == 0
+    # alpha == 0 never reads A or B, so NULL is fine there -- but that would launch; only validate
+    assert "ldc" in mdg.mdg_status_string(-14) and mdg.mdg_status_string(0) == "ok"
+    assert mdg.mdg_sgemm_variant(-1, **ok) == mdg.ERR_BAD_VARIANT
+
+
+def test_legality_rules():
+    vs = mdg.variants()
+    n = len(vs)
+    # variant 0 is legal for anything (soundness): odd sizes, unaligned pointers, huge N
+    for M, N, K in ((1, 1, 1), (7, 3, 1), (8191, 5, 13), (1, 2 ** 31 - 1, 1), (2 ** 31 - 1, 1, 1)):
+        assert mdg.mdg_variant_legal(0, 1, 0, M, N, K, K, K, M, 4, 4, 4) == 1
+    assert mdg.mdg_variant_legal(n, 0, 0, 1, 1, 1, 1, 1, 1) == mdg.ERR_BAD_VARIANT
+    mdg.mdg_set_workspace(0, 0)
+    for v in vs:
+        need = mdg.mdg_workspace_bytes(v["id"], 100, 50, 4096)
+        assert need == (v["split_k"] * 100 * 50 * 4 if v["split_k"] > 1 else 0)
+        if v["split_k"] > 1:
+            assert mdg.mdg_variant_legal(v["id"], 0, 0, 100, 4, 4096, 100, 4096, 100) == 0  # no workspace registered
+        if v["family"] == mdg.FAMILY_SKINNY:
+            assert mdg.mdg_variant_legal(v["id"], 0, 0, 100, 4 * v["sub_n"] + 1, 64, 100, 64, 100) == 0
+    # a fake (never dereferenced) workspace makes split-K legal when every slice owns a K step
+    assert mdg.mdg_set_workspace(1 << 20, 1 << 30) == 0
+    try:
+        for v in vs:
+            if v["split_k"] > 1 and v["family"] == mdg.FAMILY_TILED:
+                kmin = v["split_k"] * v["tile_k"]
+                assert mdg.mdg_variant_legal(v["id"], 0, 0, 64, 64, kmin, 64, kmin, 64) == 1
+                assert mdg.mdg_variant_legal(v["id"], 0, 0, 64, 64, kmin - v["tile_k"], 64, kmin, 64) == 0
+    finally:
+        mdg.mdg_set_workspace(0, 0)
+    assert mdg.mdg_set_workspace(12, 1024) != 0  # unaligned
+
+
+def test_selectors_return_valid_ids_everywhere():
+    n = mdg.mdg_variant_count()
+    assert isinstance(mdg.mdg_selector_name(), str)
+    for M in (1, 2, 63, 64, 65, 1000, 4096, 8192):
+        for N in (1, 17, 512, 8192):
+            for K in (1, 27, 1024, 8192):
+                for tA in (0, 1):
+                    for tB in (0, 1):
+                        assert 0 <= mdg.mdg_select(tA, tB, M, N, K) < n
+                        assert 0 <= mdg.mdg_select_default(tA, tB, M, N, K) < n
+    ns = mdg.mdg_time_select_ns([0, 1], [1, 0], [64, 4096], [64, 4096], [64, 4096], iters=1000)
+    assert 0 < ns < 1e5
