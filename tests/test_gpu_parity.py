@@ -145,7 +145,8 @@ def test_special_scalars_degenerate_sizes_and_layouts(layout):
         st, got, A, B, C0 = gu.run_case(case)
         assert st == 0 and np.array_equal(got, C0, equal_nan=True)
     # a row-major problem with both transposes and padded leading dimensions
-    case = GemmCase(130, 75, 310, TR, TR, 1.5, -0.5, layout=layout, lda=133, ldb=312, ldc=79, seed=9, name="TT-padded")
+    base = GemmCase(130, 75, 310, TR, TR, 1.5, -0.5, layout=layout, seed=9, name="TT-padded").resolved()
+    case = GemmCase(**{**base.__dict__, "lda": base.lda + 3, "ldb": base.ldb + 2, "ldc": base.ldc + 4})
     for variant in [None] + gu.legal_variants(case)[::5]:
         st, got, A, B, C0 = gu.run_case(case, variant=variant)
         assert st == 0
