@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the on-line hot path on one MI355X.
+
+A step is one pass of the whole path -- validation, decision-tree selection,
+legality check, kernel launch(es) -- over the square sweep: M = N = K in
+{256 ... 8192}, all four transpose combinations, alpha = 1, beta = 0.5 (24
+SGEMM calls through mdg_sgemm).  Operands are seeded synthetic data, resident
+in HBM before the timed region.  Prints ONE JSON line.
+
+  value        geometric mean over the 24 shapes of 2MNK / (median time of that shape), TFLOP/s
+  roofline     for the kernel symbol that takes the most time: algorithmic flops / measured duration
+               of its launches (HIP events on the launch stream, inside the timed steps) vs the MI355X
+               fp32 matrix peak
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload (reported, not a target)
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_MATRIX_PEAK_TFLOPS = 157.3  # MI355X datasheet, dense fp32 matrix
+HBM_PEAK_GBS = 8000.0
+
+
+def geomean(xs):
+    xs = list(xs)
+    return math.exp(sum(math.log(x) for x in xs) / len(xs)) if xs else float("nan")
+
+
+def kernel_symbol(desc, tA, tB):
+    """Name of the GPU kernel a variant launches for these transposes (matches the rocprofv3 kernel trace)."""
+    b = lambda x: "true" if x else "false"
+    if desc["family"] == 1:
+        wgm, wgn = desc["tile_m"] // desc["sub_m"], desc["tile_n"] // desc["sub_n"]
+        return f"tiled_kernel<{desc['tile_m']}, {desc['tile_n']}, {desc['tile_k']}, {wgm}, {wgn}, {b(tA)}, {b(tB)}>"
+    if desc["family"] == 0:
+        return f"direct_kernel<{desc['sub_m']}, {desc['sub_n']}, {b(desc['lds'])}, {b(tA)}, {b(tB)}>"
+    return f"skinny_{'t' if tA else 'n'}_kernel<{desc['sub_n']}, {b(tB)}>"
+
+
+def cpu_baseline(sample_n=4096):
+    """The oracle, as it stands, on the n = sample_n cases of the sweep (all four transpose combinations)."""
+    import numpy as np  # noqa: F401
+    from oracle import gemm_oracle as go
+    from paper_1806_07060_amd import workloads as wl
+    flops, secs = 0.0, 0.0
+    for case in wl.config1(sizes=(sample_n,)):
+        c = case.resolved()
+        A, B, C0 = wl.make_operands(c, poison=False)
+        t0 = time.perf_counter()
+        st = go.sgemm(c.layout, c.transA, c.transB, c.M, c.N, c.K, c.alpha, A, c.lda, B, c.ldb, c.beta, C0, c.ldc)
+        secs += time.perf_counter() - t0
+        assert st == 0
+        flops += c.flops()
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": go.max_threads(), "kind": "oracle",
+            "sample": f"square sweep cases with M=N=K={sample_n}, all four transpose combinations, full matrices "
+                      f"({secs:.1f} s of CPU time)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing (profiling runs)")
+    ap.add_argument("--sizes", type=str, default="256,512,1024,2048,4096,8192")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sharding design is described in "
+              "DESIGN.md, nothing here uses a second GPU)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1806_07060_amd import binding as mdg
+    from paper_1806_07060_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    mdg.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    sizes = tuple(int(s) for s in args.sizes.split(","))
+    cases = [c.resolved() for c in wl.config1(sizes=sizes)]
+    variants = mdg.variants()
+
+    ws = torch.empty(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB of split-K workspace
+    assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0
+
+    dev = []
+    for c in cases:
+        A, B, C0 = wl.make_operands(c, poison=False)
+        dev.append(tuple(torch.from_numpy(x).cuda() for x in (A, B, C0)))
+        del A, B, C0
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    sptr = stream.cuda_stream
+
+    def one_step(events=None):
+        for i, (c, (dA, dB, dC)) in enumerate(zip(cases, dev)):
+            if events is not None:
+                events[i][0].record(stream)
+            st = mdg.mdg_sgemm(c.layout, c.transA, c.transB, c.M, c.N, c.K, c.alpha, dA.data_ptr(), c.lda,
+                               dB.data_ptr(), c.ldb, c.beta, dC.data_ptr(), c.ldc, sptr)
+            if st != 0:
+                raise RuntimeError(f"{c.name}: {mdg.mdg_status_string(st)}")
+            if events is not None:
+                events[i][1].record(stream)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in cases]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(ev[s])
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+
+    per_case_ms = np.array([[ev[s][i][0].elapsed_time(ev[s][i][1]) for i in range(len(cases))]
+                            for s in range(args.steps)])
+    med_ms = np.median(per_case_ms, axis=0)
+    tflops = np.array([c.flops() / (m * 1e-3) / 1e12 for c, m in zip(cases, med_ms)])
+
+    # which kernel each call ran (selector, then fallback to variant 0 if illegal), grouped by kernel symbol
+    groups = {}
+    chosen = []
+    for i, c in enumerate(cases):
+        v = mdg.mdg_select(c.tA(), c.tB(), c.M, c.N, c.K)
+        if mdg.mdg_variant_legal(v, c.tA(), c.tB(), c.M, c.N, c.K, c.lda, c.ldb, c.ldc, dev[i][0].data_ptr(),
+                                 dev[i][1].data_ptr(), dev[i][2].data_ptr()) != 1:
+            v = 0
+        chosen.append(v)
+        sym = kernel_symbol(variants[v], c.tA(), c.tB())
+        g = groups.setdefault(sym, {"ms": 0.0, "flops": 0.0, "launches": 0, "bytes": 0.0})
+        g["ms"] += float(per_case_ms[:, i].sum())
+        g["flops"] += float(c.flops()) * args.steps
+        g["bytes"] += float(c.algorithmic_bytes()) * args.steps
+        g["launches"] += args.steps
+    dom_sym, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dom_sym, {}).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    large = [t for c, t in zip(cases, tflops) if c.M >= 4096]
+    sel_eval = None
+    epath = os.path.join(ROOT, "paper_1806_07060_amd", "tuning", "results", "selector_eval.json")
+    if os.path.exists(epath):
+        try:
+            sel_eval = json.load(open(epath))
+        except Exception:
+            sel_eval = None
+
+    out = {
+        "metric": "SGEMM TFLOP/s geomean over shape sweep; % of exhaustive-best; % FP32 peak",
+        "value": float(geomean(tflops)),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": total_s * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "square fp32 SGEMM sweep M=N=K in {" + ",".join(map(str, sizes)) + "}, column-major, "
+                               "NN/NT/TN/TT, alpha=1, beta=0.5, U[-1,1] operands, tight leading dimensions "
+                               f"({len(cases)} calls per step through mdg_sgemm)",
+                   "selector": mdg.mdg_selector_name()},
+        "aggregate_tflops": float(sum(c.flops() for c in cases) * args.steps / total_s / 1e12),
+        "pct_fp32_peak_large": float(100.0 * geomean(large) / FP32_MATRIX_PEAK_TFLOPS) if large else None,
+        "pct_exhaustive_best_heldout": (sel_eval or {}).get("heldout_geomean_pct"),
+        "per_shape": [{"case": c.name, "variant": variants[v]["name"], "ms": float(m), "tflops": float(t)}
+                      for c, v, m, t in zip(cases, chosen, med_ms, tflops)],
+        "roofline": {"bound": "mfma", "achieved": float(achieved), "peak": FP32_MATRIX_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": float(achieved / FP32_MATRIX_PEAK_TFLOPS), "traffic": traffic, "kernel": dom_sym,
+                     "launches": dom["launches"], "avg_launch_ms": dom["ms"] / dom["launches"],
+                     "algorithmic_flops_per_launch": dom["flops"] / dom["launches"],
+                     "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"]},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    mdg.mdg_set_workspace(0, 0)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

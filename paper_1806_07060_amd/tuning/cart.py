@@ -1,0 +1,230 @@
+"""Off-line phase, step 2: labels, CART decision trees and the ratio metrics (numpy, vectorised).
+
+Follows Section 3 ('Datasets', 'Model and code generation'), Section 4.2 (the
+hyper-parameters H = maximum height and L = minimum samples per leaf) and
+Section 5.2 (accuracy and DTPR) of the paper:
+
+  label(s)   = argmax_a f_a(s) = the variant with the smallest measured time
+  tree       = CART on the integer features (M, N, K, tA, tB), Gini impurity
+  DTPR       = mean over inputs of f_predicted / f_best
+
+Rules fixed where the paper leaves them open: fractional L = ceil(L * n)
+samples; an impure node below height H is split whenever some split leaves L
+samples on both sides (also at zero gain); thresholds are floor(midpoint) of
+consecutive distinct values, tested as feature <= threshold; ties go to the
+lowest feature index, then the lowest threshold; majority ties to the lowest
+variant id; an illegal prediction is priced as the fallback variant.  Split
+scores are compared exactly (integer arithmetic), so the tree is a pure
+function of the table.
+
+Leaf labels: 'majority' (plain CART) or 'logratio' (the variant maximising the
+summed log performance ratio over the leaf's training inputs, which prices a
+misclassification by what it costs -- the weakness Section 5.2 points out for
+accuracy-driven trees).
+"""
+from fractions import Fraction
+import math
+
+import numpy as np
+
+FEATURES = ("M", "N", "K", "tA", "tB")
+H_SET = (1, 2, 4, 8, None)
+L_SET = (1, 2, 4, 0.1, 0.2, 0.3, 0.4, 0.5)
+
+
+def model_name(H, L):
+    return f"h{'Max' if H is None else H}-L{L}"
+
+
+def labels_from_table(times):
+    """argmin over variants per row (first minimum = lowest id on ties)."""
+    return np.argmin(np.asarray(times, dtype=np.float64), axis=1).astype(np.int64)
+
+
+def min_samples_leaf(L, n_train):
+    if isinstance(L, float) and 0.0 < L < 1.0:
+        return max(1, math.ceil(Fraction(L).limit_denominator(1000) * n_train))
+    return max(1, int(L))
+
+
+def effective_times(times, fallback=0):
+    """Times with illegal entries (inf) replaced by the fallback variant's time of the same row."""
+    T = np.asarray(times, dtype=np.float64)
+    fb = T[:, [fallback]]
+    return np.where(np.isfinite(T), T, fb)
+
+
+def ratios(times, pred, fallback=0):
+    """f_pred / f_best per row = t_best / t_pred (with the fallback rule)."""
+    T = np.asarray(times, dtype=np.float64)
+    E = effective_times(T, fallback)
+    rows = np.arange(T.shape[0])
+    return T.min(axis=1) / E[rows, np.asarray(pred)]
+
+
+def dtpr(times, pred, fallback=0):
+    return float(np.mean(ratios(times, pred, fallback)))
+
+
+def geomean_ratio(times, pred, fallback=0):
+    return float(np.exp(np.mean(np.log(ratios(times, pred, fallback)))))
+
+
+def accuracy(pred, labels):
+    return float(np.mean(np.asarray(pred) == np.asarray(labels)))
+
+
+class Tree:
+    """Flat arrays: node i is a leaf iff feature[i] < 0."""
+
+    def __init__(self):
+        self.feature, self.threshold, self.left, self.right, self.label, self.n = [], [], [], [], [], []
+
+    def _new(self, n):
+        for a in (self.feature, self.threshold, self.left, self.right, self.label):
+            a.append(-1)
+        self.n.append(n)
+        return len(self.n) - 1
+
+    def predict(self, X):
+        X = np.asarray(X, dtype=np.int64).reshape(-1, len(FEATURES))
+        feature, threshold = np.array(self.feature), np.array(self.threshold)
+        left, right, label = np.array(self.left), np.array(self.right), np.array(self.label)
+        node = np.zeros(X.shape[0], dtype=np.int64)
+        active = feature[node] >= 0
+        while active.any():
+            f = feature[node[active]]
+            go_left = X[active, f] <= threshold[node[active]]
+            node[active] = np.where(go_left, left[node[active]], right[node[active]])
+            active = feature[node] >= 0
+        return label[node]
+
+    def stats(self):
+        leaves = [i for i, f in enumerate(self.feature) if f < 0]
+
+        def depth(i):
+            return 0 if self.feature[i] < 0 else 1 + max(depth(self.left[i]), depth(self.right[i]))
+
+        return {"leaves": len(leaves), "height": depth(0), "classes": sorted({self.label[i] for i in leaves}),
+                "min_leaf_samples": min(self.n[i] for i in leaves)}
+
+    def to_nested(self):
+        """Nested-dict form (same shape as the oracle's trees; used by tests and the code generator)."""
+        def rec(i):
+            if self.feature[i] < 0:
+                return {"leaf": int(self.label[i]), "n": int(self.n[i])}
+            return {"feature": int(self.feature[i]), "threshold": int(self.threshold[i]), "n": int(self.n[i]),
+                    "left": rec(self.left[i]), "right": rec(self.right[i])}
+        return rec(0)
+
+
+def _best_split(X, y_idx, idx, n_classes, L_abs):
+    """(feature, threshold) maximising SL/nL + SR/nR exactly, or None."""
+    n = idx.size
+    best = None  # (Fraction score, feature, threshold)
+    for f in range(X.shape[1]):
+        xs = X[idx, f]
+        order = np.argsort(xs, kind="stable")
+        xs = xs[order]
+        ys = y_idx[idx][order]
+        onehot = np.zeros((n, n_classes), dtype=np.int64)
+        onehot[np.arange(n), ys] = 1
+        cum = np.cumsum(onehot, axis=0)[:-1]  # counts left of a cut after position pos
+        tot = cum[-1] + onehot[-1] if n > 1 else onehot[0]
+        nL = np.arange(1, n, dtype=np.int64)
+        nR = n - nL
+        valid = (xs[:-1] != xs[1:]) & (nL >= L_abs) & (nR >= L_abs)
+        if not valid.any():
+            continue
+        SL = np.sum(cum * cum, axis=1)
+        SR = np.sum((tot - cum) ** 2, axis=1)
+        score = SL / nL + SR / nR
+        score[~valid] = -1.0
+        top = score.max()
+        cand = np.flatnonzero(valid & (score >= top * (1.0 - 1e-9)))
+        for pos in cand:  # exact comparison among the float near-ties, in threshold order
+            s = Fraction(int(SL[pos]), int(nL[pos])) + Fraction(int(SR[pos]), int(nR[pos]))
+            if best is None or s > best[0]:
+                best = (s, f, (int(xs[pos]) + int(xs[pos + 1])) // 2)
+    return None if best is None else (best[1], best[2])
+
+
+def fit_cart(X, times, H=None, L=1, leaf_rule="majority", fallback=0, labels=None):
+    """Grow a tree on features X [n, 5] and the timing table `times` [n, V]."""
+    X = np.asarray(X, dtype=np.int64)
+    T = np.asarray(times, dtype=np.float64)
+    y = labels_from_table(T) if labels is None else np.asarray(labels, dtype=np.int64)
+    classes, y_idx = np.unique(y, return_inverse=True)
+    L_abs = min_samples_leaf(L, X.shape[0])
+    logr = None
+    if leaf_rule == "logratio":
+        logr = np.log(T.min(axis=1, keepdims=True) / effective_times(T, fallback))
+    tree = Tree()
+
+    def leaf_label(idx):
+        if leaf_rule == "majority":
+            cnt = np.bincount(y_idx[idx], minlength=classes.size)
+            return int(classes[np.argmax(cnt)])  # first maximum = lowest id
+        return int(np.argmax(np.sum(logr[idx], axis=0)))
+
+    def grow(idx, depth):
+        node = tree._new(int(idx.size))
+        pure = np.all(y_idx[idx] == y_idx[idx[0]])
+        sp = None
+        if not pure and (H is None or depth < H) and idx.size >= 2 * L_abs:
+            sp = _best_split(X, y_idx, idx, classes.size, L_abs)
+        if sp is None:
+            tree.label[node] = leaf_label(idx)
+            return node
+        f, thr = sp
+        tree.feature[node], tree.threshold[node] = f, thr
+        go_left = X[idx, f] <= thr
+        tree.left[node] = grow(idx[go_left], depth + 1)
+        tree.right[node] = grow(idx[~go_left], depth + 1)
+        return node
+
+    grow(np.arange(X.shape[0]), 0)
+    return tree
+
+
+def sweep(X_train, T_train, X_test, T_test, leaf_rule="majority", fallback=0, H_set=H_SET, L_set=L_SET):
+    """One tree per (H, L) (Section 5): the per-model statistics the paper tabulates."""
+    y_test = labels_from_table(T_test)
+    rows = []
+    for H in H_set:
+        for L in L_set:
+            tree = fit_cart(X_train, T_train, H, L, leaf_rule, fallback)
+            pred = tree.predict(X_test)
+            st = tree.stats()
+            rows.append({"name": model_name(H, L), "H": H, "L": L, "leaf_rule": leaf_rule,
+                         "accuracy": accuracy(pred, y_test), "dtpr": dtpr(T_test, pred, fallback),
+                         "geomean": geomean_ratio(T_test, pred, fallback), "leaves": st["leaves"],
+                         "height": st["height"], "classes": st["classes"], "tree": tree})
+    return rows
+
+
+def cross_validate(X, T, H, L, leaf_rule, fallback=0, folds=5):
+    """Mean held-out log ratio over `folds` contiguous folds of the (already shuffled) training set."""
+    X = np.asarray(X, dtype=np.int64)
+    T = np.asarray(T, dtype=np.float64)
+    n = X.shape[0]
+    edges = np.linspace(0, n, folds + 1).astype(int)
+    logs = []
+    for k in range(folds):
+        test = np.arange(edges[k], edges[k + 1])
+        train = np.concatenate([np.arange(0, edges[k]), np.arange(edges[k + 1], n)])
+        tree = fit_cart(X[train], T[train], H, L, leaf_rule, fallback)
+        logs.append(np.log(ratios(T[test], tree.predict(X[test]), fallback)))
+    return float(np.exp(np.mean(np.concatenate(logs))))
+
+
+def select_model(X_train, T_train, fallback=0, folds=5, H_set=H_SET, L_set=L_SET, leaf_rules=("majority", "logratio")):
+    """Choose (H, L, leaf rule) by cross-validation inside the training set; the held-out set is not touched."""
+    table = []
+    for rule in leaf_rules:
+        for H in H_set:
+            for L in L_set:
+                table.append({"name": model_name(H, L), "H": H, "L": L, "leaf_rule": rule,
+                              "cv_geomean": cross_validate(X_train, T_train, H, L, rule, fallback, folds)})
+    best = max(table, key=lambda r: r["cv_geomean"])  # first maximum in sweep order
+    return best, table

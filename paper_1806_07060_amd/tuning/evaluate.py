@@ -1,0 +1,94 @@
+"""Off-line phase, last step: score the selector that is compiled into the library.
+
+  python -m paper_1806_07060_amd.tuning.evaluate
+
+Predictions come from the library itself (mdg_select / mdg_select_default
+through the C ABI), so what is scored is the generated if-then-else, not the
+Python tree.  Against the timing tables of the tuning run it reports, per
+dataset (Section 5.2 of the paper):
+  accuracy            right predictions / inputs
+  DTPR                arithmetic mean of  f_model / f_peak   ("peak" = best variant of the exhaustive run)
+  geomean             geometric mean of the same ratio (the figure this build is judged on)
+  DTTR                mean of  f_model / f_default  (model against the traditional default dispatch)
+  max speed-up        largest f_model / f_default
+and the cost of the tree traversal next to the kernel times (Section 5.3).
+Writes results/selector_eval.json.
+"""
+import json
+import os
+
+import numpy as np
+
+from . import cart
+from .train import RESULTS, load_table, split
+from .. import binding as mdg
+
+
+def predict_with_library(X, default=False):
+    fn = mdg.mdg_select_default if default else mdg.mdg_select
+    return np.array([fn(int(r[3]), int(r[4]), int(r[0]), int(r[1]), int(r[2])) for r in X], dtype=np.int64)
+
+
+def score(X, T, fallback=0):
+    pred = predict_with_library(X)
+    dflt = predict_with_library(X, default=True)
+    y = cart.labels_from_table(T)
+    E = cart.effective_times(T, fallback)
+    rows = np.arange(T.shape[0])
+    t_model, t_default, t_best = E[rows, pred], E[rows, dflt], T.min(axis=1)
+    r = t_best / t_model
+    return {
+        "inputs": int(T.shape[0]),
+        "accuracy": cart.accuracy(pred, y),
+        "dtpr": float(np.mean(r)),
+        "geomean": float(np.exp(np.mean(np.log(r)))),
+        "min_ratio": float(r.min()),
+        "fallback_used": int(np.sum(~np.isfinite(T[rows, pred]))),
+        "dttr": float(np.mean(t_default / t_model)),
+        "dttr_geomean": float(np.exp(np.mean(np.log(t_default / t_model)))),
+        "max_speedup_vs_default": float(np.max(t_default / t_model)),
+        "default_geomean_vs_peak": float(np.exp(np.mean(np.log(t_best / t_default)))),
+        "distinct_predicted": int(np.unique(pred).size),
+        "distinct_best": int(np.unique(y).size),
+    }
+
+
+def main():
+    mdg.lib()
+    out = {"selector": mdg.mdg_selector_name(), "variants": mdg.mdg_variant_count(), "datasets": {}}
+    p4 = os.path.join(RESULTS, "timings_cfg4.csv")
+    tab4 = load_table(p4)
+    assert tab4["variants"] == [v["name"] for v in mdg.variants()], "timing table does not match the variant table"
+    tr, te = split(tab4)
+    out["datasets"]["random_sweep_train"] = score(tab4["X"][tr], tab4["T"][tr])
+    out["datasets"]["random_sweep_heldout"] = score(tab4["X"][te], tab4["T"][te])
+    for key, fn in (("square_sweep", "timings_cfg1.csv"), ("skinny_fc", "timings_cfg2.csv"),
+                    ("conv_lowered", "timings_cfg3.csv")):
+        p = os.path.join(RESULTS, fn)
+        if os.path.exists(p):
+            t = load_table(p)
+            out["datasets"][key] = score(t["X"], t["T"])
+    held = out["datasets"]["random_sweep_heldout"]
+    out["heldout_geomean_pct"] = 100.0 * held["geomean"]
+    out["heldout_dtpr"] = held["dtpr"]
+
+    # selector overhead (Section 5.3): host nanoseconds per traversal vs the time of the selected kernel
+    Xte, Tte = tab4["X"][te], tab4["T"][te]
+    ns = mdg.mdg_time_select_ns(Xte[:, 3], Xte[:, 4], Xte[:, 0], Xte[:, 1], Xte[:, 2], iters=2000)
+    pred = predict_with_library(Xte)
+    t_model = cart.effective_times(Tte)[np.arange(Tte.shape[0]), pred]
+    frac = ns * 1e-9 / t_model
+    out["selector_overhead"] = {"ns_per_call": ns, "mean_pct_of_call": float(100 * frac.mean()),
+                                "max_pct_of_call": float(100 * frac.max())}
+    for k, v in out["datasets"].items():
+        print(f"{k:22s} n={v['inputs']:5d} acc={100 * v['accuracy']:5.1f}% DTPR={v['dtpr']:.3f} geomean={v['geomean']:.3f} "
+              f"min={v['min_ratio']:.2f} DTTR={v['dttr']:.3f} max-speedup={v['max_speedup_vs_default']:.2f}x "
+              f"default/peak={v['default_geomean_vs_peak']:.3f}")
+    print(f"selector: {out['selector']}  traversal {ns:.1f} ns/call = {out['selector_overhead']['mean_pct_of_call']:.3f}% "
+          f"of a call on average (max {out['selector_overhead']['max_pct_of_call']:.3f}%)")
+    with open(os.path.join(RESULTS, "selector_eval.json"), "w") as f:
+        json.dump(out, f, indent=1)
+
+
+if __name__ == "__main__":
+    main()

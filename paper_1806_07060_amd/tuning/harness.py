@@ -1,0 +1,180 @@
+"""Off-line phase, step 1: build the dataset D by timing every variant on every input.
+
+Section 4.1 of the paper builds each dataset entry by running the tuner over
+the whole search space of both kernels for a triple (M, N, K) and keeping the
+best; here the search space is the library's variant table and the *whole row*
+of times is kept (the ratio metrics of Section 5.2 need the time of the
+predicted variant, not only the label).  Unlike the paper's tuner, which
+reports kernel time only, a time here is the whole call: the kernel plus any
+pass the variant needs (split-K reduce).
+
+Protocol per (input, variant), all through the library's own event-timing
+entry point (mdg_time_calls):
+  1. one probe call (after one warm-up) estimates the time t;
+  2. if t exceeds `prune` x the best time seen so far for this input the
+     estimate is recorded and the variant is not measured further (it cannot
+     be the label and, being that slow, is priced well enough by one call);
+  3. otherwise `spans` spans of `reps` back-to-back calls, reps chosen so a
+     span lasts about `span_ms`; the median span is recorded.
+Calls rotate through several operand sets so that inputs are not served from
+cache left by the previous call (as many sets as fit 600 MB, at most 32).
+
+Writes a CSV, one row per input: index, name, M, N, K, tA, tB, alpha, beta,
+then seconds per variant (inf = illegal).  Rows already in the file are
+skipped, so a run can be continued.
+"""
+import argparse
+import csv
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+from .. import binding as mdg
+from .. import workloads as wl
+
+POOL_BYTES = 640 << 20
+MAX_SETS = 32
+
+
+def _align(n, a=64):
+    return (n + a - 1) // a * a
+
+
+class Pools:
+    """Device pools for A, B, C (seeded U[-1,1] data; timing does not depend on the values)."""
+
+    def __init__(self, torch, floats_each):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(wl.BASE_SEED)
+        self.torch = torch
+        self.n = floats_each
+        self.A = torch.rand(floats_each, device="cuda", generator=g) * 2 - 1
+        self.B = torch.rand(floats_each, device="cuda", generator=g) * 2 - 1
+        self.C = torch.rand(floats_each, device="cuda", generator=g) * 2 - 1
+
+    def layout(self, case):
+        c = case.resolved()
+        na = wl.buffer_len(c.layout, c.a_shape(), c.lda)
+        nb = wl.buffer_len(c.layout, c.b_shape(), c.ldb)
+        nc = wl.buffer_len(c.layout, c.c_shape(), c.ldc)
+        sa, sb, sc = _align(na), _align(nb), _align(nc)
+        foot = 4 * (na + nb + nc)
+        n_sets = max(1, min(MAX_SETS, math.ceil(600e6 / max(foot, 1)), self.n // max(sa, sb, sc)))
+        return n_sets, sa, sb, sc
+
+
+def time_variant(v, case, pools, n_sets, sa, sb, sc, stream, warmup, reps, spans):
+    c = case
+    st, ms = mdg.mdg_time_calls(v, c.tA(), c.tB(), c.M, c.N, c.K, c.alpha, pools.A.data_ptr(), c.lda,
+                                pools.B.data_ptr(), c.ldb, c.beta, pools.C.data_ptr(), c.ldc, n_sets, sa, sb, sc,
+                                warmup, reps, spans, stream)
+    if st != 0:
+        raise RuntimeError(f"variant {v} on {c.name}: {mdg.mdg_status_string(st)}")
+    return float(np.median(ms)) * 1e-3
+
+
+def measure_case(case, pools, stream, variants, span_ms=1.0, spans=3, prune=6.0, max_reps=200):
+    """Seconds of every variant on one column-major case (inf where illegal)."""
+    c = case.resolved()
+    assert c.layout == wl.COL_MAJOR
+    n_sets, sa, sb, sc = pools.layout(c)
+    out = np.full(len(variants), np.inf)
+    best = np.inf
+    # likely-good variants first so that pruning bites early
+    order = sorted(range(len(variants)), key=lambda v: (variants[v]["family"] != mdg.FAMILY_TILED, v))
+    for v in order:
+        if mdg.mdg_variant_legal(v, c.tA(), c.tB(), c.M, c.N, c.K, c.lda, c.ldb, c.ldc, pools.A.data_ptr(),
+                                 pools.B.data_ptr(), pools.C.data_ptr()) != 1:
+            continue
+        t = time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 1, 1, 1)
+        if t <= prune * best:
+            reps = int(min(max_reps, max(3, math.ceil(span_ms * 1e-3 / max(t, 1e-7)))))
+            t = time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 1, reps, spans)
+        out[v] = t
+        best = min(best, t)
+    return out
+
+
+def load_done(path):
+    done = {}
+    if os.path.exists(path):
+        with open(path) as f:
+            r = csv.reader(f)
+            header = next(r, None)
+            for row in r:
+                if row:
+                    done[int(row[0])] = row
+        return header, done
+    return None, done
+
+
+def cases_for(config):
+    if config == 1:
+        return [c.resolved() for c in wl.config1()]
+    if config == 2:
+        return [c.resolved() for c in wl.config2()]
+    if config == 3:
+        return [c.resolved() for c in wl.config3()]
+    if config == 4:
+        return [c.resolved() for c in wl.config4()]
+    if config == 0:
+        return [c.resolved() for c in wl.config0()]
+    raise ValueError(config)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--start", type=int, default=0)
+    ap.add_argument("--limit", type=int, default=10 ** 9)
+    ap.add_argument("--budget-s", type=float, default=1e9, help="stop cleanly after this many seconds")
+    ap.add_argument("--span-ms", type=float, default=1.0)
+    ap.add_argument("--spans", type=int, default=3)
+    ap.add_argument("--prune", type=float, default=6.0)
+    args = ap.parse_args(argv)
+
+    import torch
+    assert torch.cuda.is_available(), "the tuning run needs a GPU"
+    mdg.lib()
+    variants = mdg.variants()
+    cases = cases_for(args.config)
+    pools = Pools(torch, POOL_BYTES // 4)
+    ws = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0
+    stream = torch.cuda.current_stream().cuda_stream
+
+    os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+    header, done = load_done(args.out)
+    want_header = ["index", "name", "M", "N", "K", "tA", "tB", "alpha", "beta"] + [v["name"] for v in variants]
+    if header is not None and header != want_header:
+        raise SystemExit(f"{args.out} was written for a different variant table; move it away first")
+    t0 = time.time()
+    with open(args.out, "a", newline="") as f:
+        w = csv.writer(f)
+        if header is None:
+            w.writerow(want_header)
+        n_new = 0
+        for i, c in enumerate(cases):
+            if i < args.start or i >= args.start + args.limit or i in done:
+                continue
+            if time.time() - t0 > args.budget_s:
+                break
+            times = measure_case(c, pools, stream, variants, args.span_ms, args.spans, args.prune)
+            w.writerow([i, c.name, c.M, c.N, c.K, c.tA(), c.tB(), repr(c.alpha), repr(c.beta)] +
+                       [repr(float(t)) for t in times])
+            f.flush()
+            n_new += 1
+            if n_new % 25 == 0:
+                b = int(np.argmin(times))
+                print(f"[{time.time() - t0:7.1f}s] {i + 1}/{len(cases)} {c.name} {c.M}x{c.N}x{c.K} "
+                      f"best={variants[b]['name']} {times[b] * 1e6:.1f}us", flush=True)
+    mdg.mdg_set_workspace(0, 0)
+    print(f"done: {n_new} new rows in {time.time() - t0:.1f}s -> {args.out}", flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,132 @@
+"""Off-line phase, steps 2-3 as a command: timing table -> trees -> chosen model -> generated C++.
+
+  python -m paper_1806_07060_amd.tuning.train [--table results/timings_cfg4.csv]
+
+Reads the dataset written by the tuning run, takes the first 80 % of its
+(already shuffled) rows as the training set X and the rest as the held-out set
+Y (Section 3, 'Datasets'), trains one tree per (H, L) pair of Section 5 for
+both leaf rules and prints the table of model statistics the paper reports
+(accuracy, DTPR, leaves, height) on Y.  The model that is compiled into the
+library is chosen by 5-fold cross-validation inside X -- the paper picks the
+best DTPR on the test set itself, which leaks; Y is only used for reporting.
+Then writes csrc/mdg_select_generated.h and results/model.json.  Rebuild the
+library afterwards.
+"""
+import argparse
+import csv
+import json
+import os
+
+import numpy as np
+
+from . import cart, codegen
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+RESULTS = os.path.join(HERE, "results")
+
+
+def load_table(path):
+    """-> dict(index, names, X [n,5] int64, alpha, beta, T [n,V] seconds, variants [V] names)."""
+    with open(path) as f:
+        rows = list(csv.reader(f))
+    hdr, rows = rows[0], [r for r in rows[1:] if r]
+    rows.sort(key=lambda r: int(r[0]))
+    return {
+        "index": np.array([int(r[0]) for r in rows]),
+        "names": [r[1] for r in rows],
+        "X": np.array([[int(r[2]), int(r[3]), int(r[4]), int(r[5]), int(r[6])] for r in rows], dtype=np.int64),
+        "alpha": np.array([float(r[7]) for r in rows]),
+        "beta": np.array([float(r[8]) for r in rows]),
+        "T": np.array([[float(x) for x in r[9:]] for r in rows], dtype=np.float64),
+        "variants": hdr[9:],
+    }
+
+
+def split(table, train_fraction=0.8):
+    n = table["X"].shape[0]
+    n_train = int(round(train_fraction * n))
+    return slice(0, n_train), slice(n_train, n)
+
+
+def default_dispatch(cfg1_table, variants_meta):
+    """The traditional configuration (Section 5, 'default'): the tiled variant that is best on the 1024-cube
+    and the direct variant that is best on the 256-cube (summed log time over the four transpose cases),
+    switched at M*N*K = 512^3."""
+    X, T = cfg1_table["X"], cfg1_table["T"]
+    fam = np.array([m["family"] for m in variants_meta])
+    split_k = np.array([m["split_k"] for m in variants_meta])
+
+    def best(size, mask):
+        rows = np.flatnonzero((X[:, 0] == size) & (X[:, 1] == size) & (X[:, 2] == size))
+        score = np.sum(np.log(T[rows]), axis=0)
+        score[~mask | ~np.all(np.isfinite(T[rows]), axis=0)] = np.inf
+        return int(np.argmin(score))
+
+    tiled = best(1024, (fam == 1) & (split_k == 1))
+    direct = best(256, fam == 0)
+    return tiled, direct, 512.0 ** 3
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--table", default=os.path.join(RESULTS, "timings_cfg4.csv"))
+    ap.add_argument("--cfg1", default=os.path.join(RESULTS, "timings_cfg1.csv"))
+    ap.add_argument("--folds", type=int, default=5)
+    ap.add_argument("--no-write", action="store_true")
+    args = ap.parse_args(argv)
+
+    tab = load_table(args.table)
+    tr, te = split(tab)
+    Xtr, Ttr, Xte, Tte = tab["X"][tr], tab["T"][tr], tab["X"][te], tab["T"][te]
+    print(f"dataset: {tab['X'].shape[0]} inputs x {tab['T'].shape[1]} variants; train {Xtr.shape[0]}, held-out {Xte.shape[0]}")
+    y = cart.labels_from_table(tab["T"])
+    print(f"classes in use: {np.unique(y).size}; most frequent best variant: {tab['variants'][np.bincount(y).argmax()]}")
+
+    report = []
+    for rule in ("majority", "logratio"):
+        rows = cart.sweep(Xtr, Ttr, Xte, Tte, leaf_rule=rule)
+        print(f"\nleaf rule: {rule}\n{'model':12s} {'acc%':>6s} {'DTPR':>6s} {'geomean':>8s} {'leaves':>6s} {'height':>6s} {'classes':>7s}")
+        for r in rows:
+            print(f"{r['name']:12s} {100 * r['accuracy']:6.1f} {r['dtpr']:6.3f} {r['geomean']:8.3f} {r['leaves']:6d} "
+                  f"{r['height']:6d} {len(r['classes']):7d}")
+            report.append({k: v for k, v in r.items() if k != "tree"})
+
+    best, cv_table = cart.select_model(Xtr, Ttr, folds=args.folds)
+    print(f"\nchosen by {args.folds}-fold cross-validation on the training set: {best['name']}/{best['leaf_rule']} "
+          f"(cv geomean {best['cv_geomean']:.4f})")
+    tree = cart.fit_cart(Xtr, Ttr, best["H"], best["L"], best["leaf_rule"])
+    pred = tree.predict(Xte)
+    held = {"accuracy": cart.accuracy(pred, cart.labels_from_table(Tte)), "dtpr": cart.dtpr(Tte, pred),
+            "geomean": cart.geomean_ratio(Tte, pred)}
+    st = tree.stats()
+    print(f"held-out: accuracy {100 * held['accuracy']:.1f}%  DTPR {held['dtpr']:.4f}  geomean {held['geomean']:.4f}  "
+          f"leaves {st['leaves']} height {st['height']}")
+
+    from .. import binding as mdg
+    meta = mdg.variants()
+    assert [m["name"] for m in meta] == tab["variants"], "timing table was written for a different variant table"
+    d_tiled, d_direct, d_thr = (meta[0]["id"], 0, 512.0 ** 3)
+    if os.path.exists(args.cfg1):
+        d_tiled, d_direct, d_thr = default_dispatch(load_table(args.cfg1), meta)
+    print(f"default dispatch: tiled={meta[d_tiled]['name']} direct={meta[d_direct]['name']} threshold={d_thr:.3g}")
+
+    if not args.no_write:
+        name = f"{best['name']}/{best['leaf_rule']}"
+        nested = tree.to_nested()
+        codegen.write_header(nested, name, variant_names=tab["variants"], default_tiled=d_tiled, default_direct=d_direct,
+                             default_threshold=d_thr,
+                             provenance=f"model {name}, trained on {Xtr.shape[0]} inputs of {os.path.basename(args.table)}; "
+                                        f"{st['leaves']} leaves, height {st['height']}")
+        os.makedirs(RESULTS, exist_ok=True)
+        with open(os.path.join(RESULTS, "model.json"), "w") as f:
+            json.dump({"name": name, "H": best["H"], "L": best["L"], "leaf_rule": best["leaf_rule"],
+                       "cv_geomean": best["cv_geomean"], "heldout_at_training_time": held, "stats": st,
+                       "variants": tab["variants"], "tree": nested,
+                       "default_dispatch": {"tiled": d_tiled, "direct": d_direct, "threshold": d_thr},
+                       "sweep_on_heldout": report,
+                       "cv_table": cv_table}, f, indent=1)
+        print(f"wrote {codegen.GENERATED_HEADER} and results/model.json -- rebuild the library")
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,141 @@
+"""Parity of the product's off-line pipeline (numpy CART, metrics, code generator) with the selector oracle. CPU only.
+
+Integer work (labels, tree structure, predictions, generated code) must agree exactly; the ratio metrics to
+rounding error.  Inputs are seeded synthetic timing tables (no measured data is involved here).
+"""
+import ctypes
+import json
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import selector_oracle as so
+from paper_1806_07060_amd import workloads as wl
+from paper_1806_07060_amd.tuning import cart, codegen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _table(n, v, seed):
+    feats, times = wl.synthetic_timing_table(n, v, seed)
+    return feats, times, [tuple(int(a) for a in r) for r in feats], [list(map(float, r)) for r in times]
+
+
+@pytest.mark.parametrize("seed,n,v", [(1, 200, 8), (2, 320, 14)])
+def test_labels_and_trees_are_identical_to_the_oracle(seed, n, v):
+    X, T, Xl, Tl = _table(n, v, seed)
+    assert cart.labels_from_table(T).tolist() == so.labels_from_table(Tl)
+    y = so.labels_from_table(Tl)
+    for rule in ("majority", "logratio"):
+        for H, L in ((1, 1), (2, 4), (4, 0.1), (8, 2), (None, 1), (None, 4), (None, 0.3), (3, 0.5)):
+            ours = cart.fit_cart(X, T, H, L, rule).to_nested()
+            ref = so.fit_cart(Xl, y, H, L, rule, Tl, 0)
+            assert ours == ref, (rule, H, L)
+
+
+def test_predictions_and_metrics_match_the_oracle():
+    X, T, Xl, Tl = _table(300, 10, 3)
+    tr, te = slice(0, 240), slice(240, 300)
+    for rule in ("majority", "logratio"):
+        ours = cart.sweep(X[tr], T[tr], X[te], T[te], leaf_rule=rule)
+        ref = so.sweep(Xl[tr], Tl[tr], Xl[te], Tl[te], leaf_rule=rule)
+        assert [r["name"] for r in ours] == [r["name"] for r in ref]
+        for a, b in zip(ours, ref):
+            assert a["tree"].to_nested() == b["tree"]
+            assert a["tree"].predict(X[te]).tolist() == [so.predict(b["tree"], x) for x in Xl[te]]
+            assert a["leaves"] == b["leaves"] and a["height"] == b["height"]
+            assert a["accuracy"] == pytest.approx(b["accuracy"], abs=1e-15)
+            assert a["dtpr"] == pytest.approx(b["dtpr"], rel=1e-12)
+            assert a["geomean"] == pytest.approx(b["geomean"], rel=1e-12)
+
+
+def test_min_samples_and_names_match_the_oracle():
+    for L in cart.L_SET:
+        for n in (10, 192, 1600, 1601):
+            assert cart.min_samples_leaf(L, n) == so.min_samples_leaf(L, n)
+    assert [cart.model_name(H, L) for H in cart.H_SET for L in cart.L_SET] == \
+           [so.model_name(H, L) for H in so.H_SET for L in so.L_SET]
+
+
+def test_illegal_predictions_are_priced_as_the_fallback():
+    T = np.array([[2.0, np.inf, 1.0], [3.0, 1.0, np.inf]])
+    assert cart.ratios(T, [1, 2]).tolist() == [0.5, 1.0 / 3.0]
+    assert cart.ratios(T, [1, 2]).tolist() == [so.performance_ratio(list(T[0]), 1), so.performance_ratio(list(T[1]), 2)]
+
+
+def test_cross_validation_selects_a_model_without_the_heldout_set():
+    X, T, _, _ = _table(250, 9, 4)
+    best, table = cart.select_model(X[:200], T[:200], folds=4, H_set=(2, None), L_set=(1, 4, 0.2))
+    assert len(table) == 12 and best in table
+    assert all(0 < r["cv_geomean"] <= 1 for r in table)
+    assert best["cv_geomean"] == max(r["cv_geomean"] for r in table)
+
+
+def _compile_selector(header_text, tmp_path):
+    (tmp_path / "mdg_select_generated.h").write_text(header_text)
+    (tmp_path / "sel.cpp").write_text('#include "mdg_select_generated.h"\nextern "C" int sel(int a,int b,long long M,long long N,long long K)'
+                                      '{return mdg_generated_select(a,b,M,N,K);}\n'
+                                      'extern "C" const char* name(){return MDG_GENERATED_SELECTOR_NAME;}\n'
+                                      'extern "C" int dflt(int w){return w==0?MDG_GENERATED_DEFAULT_TILED:MDG_GENERATED_DEFAULT_DIRECT;}\n')
+    lib = tmp_path / "libsel.so"
+    subprocess.run(["g++", "-O1", "-shared", "-fPIC", "-o", str(lib), str(tmp_path / "sel.cpp")], check=True)
+    L = ctypes.CDLL(str(lib))
+    L.sel.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_longlong, ctypes.c_longlong, ctypes.c_longlong]
+    L.name.restype = ctypes.c_char_p
+    return L
+
+
+@pytest.mark.parametrize("H,L,rule", [(None, 1, "majority"), (4, 2, "logratio"), (0, 1, "majority")])
+def test_generated_cpp_equals_the_tree_everywhere(H, L, rule, tmp_path):
+    X, T, _, _ = _table(260, 11, 5)
+    tree = cart.fit_cart(X, T, H, L, rule)
+    nested = tree.to_nested()
+    text = codegen.tree_to_cpp(nested, "test-model", variant_names=[f"v{i}" for i in range(11)], default_tiled=3,
+                               default_direct=1)
+    lib = _compile_selector(text, tmp_path)
+    assert lib.name() == b"test-model" and lib.dflt(0) == 3 and lib.dflt(1) == 1
+    # all training shapes plus threshold-1 / threshold / threshold+1 probes of every internal node
+    probes = [tuple(r) for r in X.tolist()]
+    base = X[0].tolist()
+    for f, thr in codegen.internal_thresholds(nested):
+        for d in (-1, 0, 1):
+            p = list(base)
+            p[f] = thr + d
+            probes.append(tuple(p))
+            q = [1, 1, 1, 0, 0]
+            q[f] = thr + d
+            probes.append(tuple(q))
+    P = np.array(probes, dtype=np.int64)
+    want = tree.predict(P)
+    got = [lib.sel(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) for p in P]
+    assert got == want.tolist()
+    assert got == [so.predict(nested, tuple(int(x) for x in p)) for p in P]
+
+
+def test_shipped_selector_matches_the_stored_model():
+    # the header compiled into the library must be the one generated from results/model.json
+    from paper_1806_07060_amd import binding as mdg
+    path = os.path.join(ROOT, "paper_1806_07060_amd", "tuning", "results", "model.json")
+    if not os.path.exists(path):
+        pytest.skip("no trained model stored yet")
+    model = json.load(open(path))
+    assert mdg.mdg_selector_name() == model["name"]
+    assert model["variants"] == [v["name"] for v in mdg.variants()]
+    rng = np.random.default_rng(6)
+    P = np.column_stack([np.rint(2.0 ** (13 * rng.uniform(size=(3000, 3)))).astype(np.int64),
+                         rng.integers(0, 2, size=(3000, 2))])
+    extra = []
+    for f, thr in codegen.internal_thresholds(model["tree"]):
+        for d in (-1, 0, 1):
+            p = [64, 64, 64, 0, 1]
+            p[f] = max(0, thr + d)
+            extra.append(p)
+    P = np.vstack([P, np.array(extra, dtype=np.int64).reshape(-1, 5)])
+    for p in P:
+        assert mdg.mdg_select(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) == \
+            so.predict(model["tree"], tuple(int(x) for x in p))
+    d = model["default_dispatch"]
+    assert mdg.mdg_select_default(0, 0, 4096, 4096, 4096) == d["tiled"]
+    assert mdg.mdg_select_default(0, 0, 8, 8, 8) == d["direct"]
