@@ -25,6 +25,8 @@
 // transposed on their way into LDS (four 4-byte writes; the +4 padding spreads
 // them over the banks).  One barrier per K step: loads for step t+1 are issued
 // before the MFMAs of step t and written to the other stage after them.
+#include <type_traits>
+
 #include "mdg_internal.h"
 #include "mdg_variant_list.h"
 
@@ -71,16 +73,23 @@ struct OperandLoader {
 
   __device__ __forceinline__ static void load(floatx4 (&r)[kSlots], const float* __restrict__ X, int64_t ld, int mn0,
                                               int k0, int mn_lim, int k_lim, bool fast, int tid) {
+    if (fast) {
 #pragma unroll
-    for (int s = 0; s < kSlots; ++s) {
-      int mn, k;
-      coords(s, tid, mn, k);
-      mn += mn0;
-      k += k0;
-      if (fast) {
+      for (int s = 0; s < kSlots; ++s) {
+        int mn, k;
+        coords(s, tid, mn, k);
+        mn += mn0;
+        k += k0;
         const float* src = KMAJOR ? X + (int64_t)k + (int64_t)mn * ld : X + (int64_t)mn + (int64_t)k * ld;
         r[s] = *reinterpret_cast<const floatx4*>(src);
-      } else {
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < kSlots; ++s) {
+        int mn, k;
+        coords(s, tid, mn, k);
+        mn += mn0;
+        k += k0;
         floatx4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -93,6 +102,29 @@ struct OperandLoader {
         r[s] = v;
       }
     }
+  }
+
+  // Lean path for interior tiles: one work-group-uniform base pointer that moves along K
+  // (scalar registers) plus a fixed 32-bit byte offset per slot, so a K step costs no vector
+  // ALU work for addressing.  Usable when every offset inside a tile fits in 31 bits.
+  __device__ __forceinline__ static bool offsets_fit(int64_t ld) {
+    return (KMAJOR ? (int64_t)BMN : (int64_t)BK) * ld * 4 < 0x7fffffffLL;
+  }
+  __device__ __forceinline__ static void fast_offsets(uint32_t (&off)[kSlots], int64_t ld, int tid) {
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) {
+      int mn, k;
+      coords(s, tid, mn, k);
+      off[s] = (uint32_t)(4 * (KMAJOR ? (int64_t)k + (int64_t)mn * ld : (int64_t)mn + (int64_t)k * ld));
+    }
+  }
+  __device__ __forceinline__ static const char* fast_base(const float* X, int64_t ld, int mn0, int k0) {
+    return reinterpret_cast<const char*>(KMAJOR ? X + (int64_t)k0 + (int64_t)mn0 * ld : X + (int64_t)mn0 + (int64_t)k0 * ld);
+  }
+  __device__ __forceinline__ static int64_t fast_stride(int64_t ld) { return KMAJOR ? (int64_t)BK * 4 : (int64_t)BK * ld * 4; }
+  __device__ __forceinline__ static void fast_load(floatx4 (&r)[kSlots], const char* base, const uint32_t (&off)[kSlots]) {
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) r[s] = *reinterpret_cast<const floatx4*>(base + off[s]);
   }
 
   // registers -> LDS stage S[BK][BMN + kPad]
@@ -130,8 +162,16 @@ __device__ __forceinline__ void lds_read_frag(float (&dst)[F], const float* src)
   }
 }
 
+// work-groups per CU the register allocation is held to: two for the mid-size tiles (their
+// accumulators fit twice into the 512-register file), one for the 256 x 256 four-wave tile
+template <int BM, int BN, int WGM, int WGN>
+constexpr int min_blocks_per_cu() {
+  return (BM * BN / (WGM * WGN) > 128 * 64) ? 1 : 2;
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, bool TA, bool TB>
-__global__ __launch_bounds__(64 * WGM * WGN) void tiled_kernel(TiledParams p) {
+__global__ __launch_bounds__(64 * WGM * WGN, (min_blocks_per_cu<BM, BN, WGM, WGN>()))
+void tiled_kernel(TiledParams p) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -201,33 +241,80 @@ __global__ __launch_bounds__(64 * WGM * WGN) void tiled_kernel(TiledParams p) {
   const float* a_rd = As + h * LDA_S + wm * WTM + FM * pl;
   const float* b_rd = Bs + h * LDB_S + wn * WTN + FN * pl;
 
-  for (int t = 0; t < n_steps; ++t) {
-    const int buf = t & 1;
-    const bool more = (t + 1 < n_steps);
-    if (more) {
-      const int k0 = k_begin + (t + 1) * BK;
-      const bool kfull = (k0 + BK <= k_end);
-      LoadA::load(ra, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, tid);
-      LoadB::load(rb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, tid);
-    }
-    const float* a_s = a_rd + buf * A_STAGE;
-    const float* b_s = b_rd + buf * B_STAGE;
+  // One K step on LDS stage BUF.  Schedule (pinned with scheduling barriers):
+  //   - operand registers are double-buffered: the LDS reads of sub-step kk+2 are issued before
+  //     the MFMAs of sub-step kk, so their latency hides behind FM*FN matrix instructions;
+  //   - the global loads of the next K step are issued once the first block of MFMAs is queued;
+  //   - their LDS stores (other stage) are issued in front of the last block of MFMAs, so the
+  //     matrix pipe still has work while the wave writes LDS and reaches the barrier.
+  // `load_next` issues the loads, `have_next` says whether there is anything to store.
+  auto k_step = [&](auto buf_tag, auto&& load_next, bool have_next) __attribute__((always_inline)) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const float* a_s = a_rd + BUF * A_STAGE;
+    const float* b_s = b_rd + BUF * B_STAGE;
+    float af[2][FM], bf[2][FN];
+    lds_read_frag<FM>(af[0], a_s);
+    lds_read_frag<FN>(bf[0], b_s);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float af[FM], bf[FN];
-      lds_read_frag<FM>(af, a_s + kk * LDA_S);
-      lds_read_frag<FN>(bf, b_s + kk * LDB_S);
+      const int cur = (kk >> 1) & 1;
+      if (kk + 2 < BK) {
+        lds_read_frag<FM>(af[cur ^ 1], a_s + (kk + 2) * LDA_S);
+        lds_read_frag<FN>(bf[cur ^ 1], b_s + (kk + 2) * LDB_S);
+      }
+      if (kk == 2) load_next();
+      if (kk == BK - 2 && have_next) {
+        LoadA::store(ra, As + (BUF ^ 1) * A_STAGE, tid);
+        LoadB::store(rb, Bs + (BUF ^ 1) * B_STAGE, tid);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int c = 0; c < FN; ++c)
 #pragma unroll
         for (int b = 0; b < FM; ++b)
-          acc[c][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[c], af[b], acc[c][b], 0, 0, 0);
-    }
-    if (more) {
-      LoadA::store(ra, As + (buf ^ 1) * A_STAGE, tid);
-      LoadB::store(rb, Bs + (buf ^ 1) * B_STAGE, tid);
+          acc[c][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[cur][c], af[cur][b], acc[c][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
+  };
+  using Buf0 = std::integral_constant<int, 0>;
+  using Buf1 = std::integral_constant<int, 1>;
+
+  int t = 0;
+  // ---- interior tiles: K steps whose successor is a full, aligned tile use the lean loads
+  const int n_full = (a_full && b_full && LoadA::offsets_fit(p.lda) && LoadB::offsets_fit(p.ldb))
+                         ? (k_end - k_begin) / BK : 0;
+  if (n_full > 2) {
+    uint32_t offa[LoadA::kSlots], offb[LoadB::kSlots];
+    LoadA::fast_offsets(offa, p.lda, tid);
+    LoadB::fast_offsets(offb, p.ldb, tid);
+    const char* pa = LoadA::fast_base(p.A, p.lda, m0, k_begin + BK);
+    const char* pb = LoadB::fast_base(p.B, p.ldb, n0, k_begin + BK);
+    const int64_t sa = LoadA::fast_stride(p.lda), sb = LoadB::fast_stride(p.ldb);
+    auto lean = [&]() __attribute__((always_inline)) {
+      LoadA::fast_load(ra, pa, offa);
+      LoadB::fast_load(rb, pb, offb);
+      pa += sa;
+      pb += sb;
+    };
+    for (; t + 2 < n_full; t += 2) {  // loads tiles t+1 and t+2, both full
+      k_step(Buf0{}, lean, true);
+      k_step(Buf1{}, lean, true);
+    }
+  }
+  // ---- everything else (edge tiles, unaligned operands, the K tail): guarded loads
+  for (; t < n_steps; ++t) {
+    const bool more = (t + 1 < n_steps);
+    auto guarded = [&]() __attribute__((always_inline)) {
+      if (more) {
+        const int k0 = k_begin + (t + 1) * BK;
+        const bool kfull = (k0 + BK <= k_end);
+        LoadA::load(ra, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, tid);
+        LoadB::load(rb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, tid);
+      }
+    };
+    if (t & 1) k_step(Buf1{}, guarded, more);
+    else k_step(Buf0{}, guarded, more);
   }
 
   // ---- epilogue
