@@ -45,12 +45,14 @@ def kernel_symbol(desc, tA, tB):
 
 
 def cpu_baseline(sample_n=4096):
-    """The oracle, as it stands, on the n = sample_n cases of the sweep (all four transpose combinations)."""
+    """The oracle, as it stands, on a bounded sample of the sweep: the n = sample_n cases NN and TN."""
     import numpy as np  # noqa: F401
     from oracle import gemm_oracle as go
     from paper_1806_07060_amd import workloads as wl
     flops, secs = 0.0, 0.0
     for case in wl.config1(sizes=(sample_n,)):
+        if case.name[-2:] not in ("NN", "TN"):
+            continue
         c = case.resolved()
         A, B, C0 = wl.make_operands(c, poison=False)
         t0 = time.perf_counter()
@@ -59,7 +61,7 @@ def cpu_baseline(sample_n=4096):
         assert st == 0
         flops += c.flops()
     return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": go.max_threads(), "kind": "oracle",
-            "sample": f"square sweep cases with M=N=K={sample_n}, all four transpose combinations, full matrices "
+            "sample": f"square sweep cases with M=N=K={sample_n}, NN and TN, full matrices "
                       f"({secs:.1f} s of CPU time)"}
 
 
@@ -70,6 +72,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing (profiling runs)")
     ap.add_argument("--sizes", type=str, default="256,512,1024,2048,4096,8192")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="instead of the benchmark, launch 5 plain device copies of BYTES (read BYTES + write BYTES "
+                         "each) and exit: the known-size kernel against which the FETCH_SIZE / WRITE_SIZE counters "
+                         "are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sharding design is described in "
@@ -82,6 +88,16 @@ def main():
     from paper_1806_07060_amd import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        n = args.copy_calibration // 4
+        src = torch.rand(n, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": n * 4, "launches": 5}))
+        return
     mdg.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     sizes = tuple(int(s) for s in args.sizes.split(","))

@@ -62,12 +62,12 @@ __global__ __launch_bounds__(256) void skinny_n_kernel(SkinnyParams p) {
   for (int j = 0; j < NB; ++j) jc[j] = min(n0 + j, p.N - 1);
 
   int k = k_begin;
-  for (; k + 8 <= k_end; k += 8) {
-    float av[8];
+  for (; k + 16 <= k_end; k += 16) {  // 16 independent loads in flight per lane
+    float av[16];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) av[u] = a[(int64_t)(k + u) * p.lda];
+    for (int u = 0; u < 16; ++u) av[u] = a[(int64_t)(k + u) * p.lda];
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < 16; ++u)
 #pragma unroll
       for (int j = 0; j < NB; ++j) acc[j] = fmaf(av[u], ld_b<TB>(p.B, p.ldb, k + u, jc[j]), acc[j]);
   }

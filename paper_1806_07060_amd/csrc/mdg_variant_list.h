@@ -33,7 +33,9 @@
   X(8, 64, 64, 16, 2, 2)       \
   X(9, 64, 64, 32, 2, 2)       \
   X(10, 32, 32, 32, 1, 1)      \
-  X(11, 256, 256, 32, 2, 4)
+  X(11, 256, 256, 32, 2, 4)     \
+  X(12, 128, 32, 32, 4, 1)      \
+  X(13, 32, 128, 32, 1, 4)
 
 // Skinny-N kernel: streams A once; NB columns of C are held per thread.
 //   X(cfg, NB)
@@ -66,6 +68,8 @@
   V(TILED, 9, 1)        \
   V(TILED, 10, 1)       \
   V(TILED, 11, 1)       \
+  V(TILED, 12, 1)       \
+  V(TILED, 13, 1)       \
   V(TILED, 2, 2)        \
   V(TILED, 4, 2)        \
   V(TILED, 4, 4)        \
@@ -77,6 +81,14 @@
   V(TILED, 10, 4)       \
   V(TILED, 10, 16)      \
   V(TILED, 10, 64)      \
+  V(TILED, 6, 2)        \
+  V(TILED, 6, 4)        \
+  V(TILED, 7, 2)        \
+  V(TILED, 7, 4)        \
+  V(TILED, 12, 4)       \
+  V(TILED, 12, 16)      \
+  V(TILED, 13, 4)       \
+  V(TILED, 13, 16)      \
   V(SKINNY, 0, 1)       \
   V(SKINNY, 1, 1)       \
   V(SKINNY, 2, 1)       \
@@ -84,4 +96,7 @@
   V(SKINNY, 0, 8)       \
   V(SKINNY, 1, 8)       \
   V(SKINNY, 2, 8)       \
-  V(SKINNY, 3, 8)
+  V(SKINNY, 3, 8)       \
+  V(SKINNY, 0, 32)      \
+  V(SKINNY, 1, 32)      \
+  V(SKINNY, 2, 32)

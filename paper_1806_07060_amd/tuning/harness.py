@@ -61,6 +61,8 @@ class Pools:
         nb = wl.buffer_len(c.layout, c.b_shape(), c.ldb)
         nc = wl.buffer_len(c.layout, c.c_shape(), c.ldc)
         sa, sb, sc = _align(na), _align(nb), _align(nc)
+        if max(sa, sb, sc) > self.n:
+            raise ValueError(f"{c.name}: an operand of {max(sa, sb, sc)} floats does not fit the {self.n}-float pool")
         foot = 4 * (na + nb + nc)
         n_sets = max(1, min(MAX_SETS, math.ceil(600e6 / max(foot, 1)), self.n // max(sa, sb, sc)))
         return n_sets, sa, sb, sc
@@ -122,12 +124,19 @@ def cases_for(config):
         return [c.resolved() for c in wl.config4()]
     if config == 0:
         return [c.resolved() for c in wl.config0()]
+    if config == 5:
+        return [c.resolved() for c in wl.config_go2()]
+    if config == 6:
+        return [c.resolved() for c in wl.config_po2()]
+    if config == 7:
+        return [c.resolved() for c in wl.config_wide()]
     raise ValueError(config)
 
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--config", type=int, default=4,
+                    help="0-4: the five workload configurations; 5: go2 grid; 6: po2 grid; 7: wide random sweep")
     ap.add_argument("--out", required=True)
     ap.add_argument("--start", type=int, default=0)
     ap.add_argument("--limit", type=int, default=10 ** 9)

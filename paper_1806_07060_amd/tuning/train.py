@@ -6,7 +6,11 @@ Reads the dataset written by the tuning run, takes the first 80 % of its
 (already shuffled) rows as the training set X and the rest as the held-out set
 Y (Section 3, 'Datasets'), trains one tree per (H, L) pair of Section 5 for
 both leaf rules and prints the table of model statistics the paper reports
-(accuracy, DTPR, leaves, height) on Y.  The model that is compiled into the
+(accuracy, DTPR, leaves, height) on Y.  Further synthetic tables (--extra: the
+go2 and po2 grids of Section 4.1, the wide sweep) are added to X only -- a
+hybrid of several generation rules, as Section 3 allows -- after dropping any
+input whose (M, N, K) occurs in the square, skinny or convolution-lowered
+evaluation sets, which stay unseen.  The model that is compiled into the
 library is chosen by 5-fold cross-validation inside X -- the paper picks the
 best DTPR on the test set itself, which leaks; Y is only used for reporting.
 Then writes csrc/mdg_select_generated.h and results/model.json.  Rebuild the
@@ -48,6 +52,23 @@ def split(table, train_fraction=0.8):
     return slice(0, n_train), slice(n_train, n)
 
 
+def training_union(tab4, extra_tables, exclude_tables, seed=180607060):
+    """X = first 80 % of the random sweep + the extra tables, minus shapes of the excluded tables; shuffled."""
+    tr, _ = split(tab4)
+    Xs, Ts, src = [tab4["X"][tr]], [tab4["T"][tr]], ["cfg4"] * tab4["X"][tr].shape[0]
+    banned = set()
+    for t in exclude_tables:
+        banned |= {tuple(r[:3]) for r in t["X"].tolist()}
+    for name, t in extra_tables:
+        keep = np.array([tuple(r[:3]) not in banned for r in t["X"].tolist()], dtype=bool)
+        Xs.append(t["X"][keep])
+        Ts.append(t["T"][keep])
+        src += [name] * int(keep.sum())
+    X, T = np.vstack(Xs), np.vstack(Ts)
+    perm = np.random.Generator(np.random.PCG64(seed)).permutation(X.shape[0])
+    return X[perm], T[perm], [src[i] for i in perm]
+
+
 def default_dispatch(cfg1_table, variants_meta):
     """The traditional configuration (Section 5, 'default'): the tiled variant that is best on the 1024-cube
     and the direct variant that is best on the 256-cube (summed log time over the four transpose cases),
@@ -71,14 +92,25 @@ def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--table", default=os.path.join(RESULTS, "timings_cfg4.csv"))
     ap.add_argument("--cfg1", default=os.path.join(RESULTS, "timings_cfg1.csv"))
+    ap.add_argument("--extra", nargs="*", default=["timings_go2.csv", "timings_wide.csv", "timings_po2.csv"],
+                    help="further tables (file names under results/) whose inputs join the training set")
+    ap.add_argument("--exclude", nargs="*", default=["timings_cfg1.csv", "timings_cfg2.csv", "timings_cfg3.csv"],
+                    help="tables whose shapes must stay out of the training set")
     ap.add_argument("--folds", type=int, default=5)
     ap.add_argument("--no-write", action="store_true")
     args = ap.parse_args(argv)
 
     tab = load_table(args.table)
     tr, te = split(tab)
-    Xtr, Ttr, Xte, Tte = tab["X"][tr], tab["T"][tr], tab["X"][te], tab["T"][te]
-    print(f"dataset: {tab['X'].shape[0]} inputs x {tab['T'].shape[1]} variants; train {Xtr.shape[0]}, held-out {Xte.shape[0]}")
+    Xte, Tte = tab["X"][te], tab["T"][te]
+    extras = [(os.path.splitext(f)[0].replace("timings_", ""), load_table(os.path.join(RESULTS, f)))
+              for f in args.extra if os.path.exists(os.path.join(RESULTS, f))]
+    excl = [load_table(os.path.join(RESULTS, f)) for f in args.exclude if os.path.exists(os.path.join(RESULTS, f))]
+    for _, t in extras:
+        assert t["variants"] == tab["variants"], "extra table was written for a different variant table"
+    Xtr, Ttr, src = training_union(tab, extras, excl)
+    print(f"dataset: {tab['X'].shape[0]} inputs x {tab['T'].shape[1]} variants; held-out {Xte.shape[0]}; "
+          f"train {Xtr.shape[0]} = " + " + ".join(f"{src.count(n)} {n}" for n in dict.fromkeys(sorted(src))))
     y = cart.labels_from_table(tab["T"])
     print(f"classes in use: {np.unique(y).size}; most frequent best variant: {tab['variants'][np.bincount(y).argmax()]}")
 
@@ -115,11 +147,13 @@ def main(argv=None):
         nested = tree.to_nested()
         codegen.write_header(nested, name, variant_names=tab["variants"], default_tiled=d_tiled, default_direct=d_direct,
                              default_threshold=d_thr,
-                             provenance=f"model {name}, trained on {Xtr.shape[0]} inputs of {os.path.basename(args.table)}; "
+                             provenance=f"model {name}, trained on {Xtr.shape[0]} inputs ("
+                                        + ", ".join(f"{src.count(n)} {n}" for n in dict.fromkeys(sorted(src))) + "); "
                                         f"{st['leaves']} leaves, height {st['height']}")
         os.makedirs(RESULTS, exist_ok=True)
         with open(os.path.join(RESULTS, "model.json"), "w") as f:
             json.dump({"name": name, "H": best["H"], "L": best["L"], "leaf_rule": best["leaf_rule"],
+                       "training_set": {n: src.count(n) for n in dict.fromkeys(sorted(src))},
                        "cv_geomean": best["cv_geomean"], "heldout_at_training_time": held, "stats": st,
                        "variants": tab["variants"], "tree": nested,
                        "default_dispatch": {"tiled": d_tiled, "direct": d_direct, "threshold": d_thr},

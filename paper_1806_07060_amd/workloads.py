@@ -233,6 +233,47 @@ def po2():
     return [(m, n, k) for m in g for n in g for k in g]
 
 
+def _dress(triples, config_index, prefix):
+    """Triples -> cases with seeded transposes, alpha and beta drawn as in the random sweep."""
+    rng = np.random.Generator(np.random.PCG64(case_seed(config_index, 0)))
+    cases = []
+    for i, (m, n, k) in enumerate(triples):
+        ta = TRANS if rng.uniform() < 0.5 else NO_TRANS
+        tb = TRANS if rng.uniform() < 0.5 else NO_TRANS
+        alpha = float(np.float32(rng.uniform(0.5, 2.0)))
+        which = int(rng.integers(0, 3))
+        beta_draw = float(np.float32(rng.uniform(-1.0, 1.0)))
+        cases.append(GemmCase(m, n, k, ta, tb, alpha, (0.0, 1.0, beta_draw)[which], dist="uniform", c0="uniform",
+                              seed=case_seed(config_index, i + 1), name=f"{prefix}/{m}x{n}x{k}"))
+    return cases
+
+
+def config_go2():
+    """The 'grid of two' triples of Section 4.1 as cases (transposes, alpha, beta seeded as in the random sweep)."""
+    return _dress(go2(), 5, "go2")
+
+
+def config_po2():
+    """The 'power of two' triples of Section 4.1 as cases."""
+    return _dress(po2(), 6, "po2")
+
+
+def config_wide(n_shapes=1000, max_flops=2 ** 38, max_bytes=1.5e9, max_operand_bytes=6e8):
+    """Wider random sweep: dimensions log-uniform in [1, 65536], rejected while the product exceeds
+    max_flops, the operands together exceed max_bytes or one of them exceeds max_operand_bytes.  Covers the large and very rectangular corner (long
+    convolution-lowered N, big squares) that the 2**32-flop cap of the main sweep leaves out."""
+    rng = np.random.Generator(np.random.PCG64(case_seed(7, 0)))
+    triples = []
+    while len(triples) < n_shapes:
+        m, n, k = (int(min(max(round(2.0 ** (16.0 * rng.uniform())), 1), 65536)) for _ in range(3))
+        if 2 * m * n * k > max_flops or 4 * (m * k + k * n + m * n) > max_bytes:
+            continue
+        if 4 * max(m * k, k * n, m * n) > max_operand_bytes:
+            continue
+        triples.append((m, n, k))
+    return _dress(triples, 7, "wide")
+
+
 # ------------------------------------------------------------------------------------------
 # synthetic timing tables for selector tests (no GPU involved)
 # ------------------------------------------------------------------------------------------
