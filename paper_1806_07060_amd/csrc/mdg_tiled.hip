@@ -23,8 +23,8 @@
 // non-contracted index contiguous).  Global loads are float4 along whichever
 // index is contiguous in memory; operands stored with k contiguous are
 // transposed on their way into LDS (four 4-byte writes; the +4 padding spreads
-// them over the banks).  One barrier per K step: loads for step t+1 are issued
-// before the MFMAs of step t and written to the other stage after them.
+// them over the banks).  One barrier per K step; global loads run two K steps
+// ahead (two register sets), LDS stages alternate.
 #include <type_traits>
 
 #include "mdg_internal.h"
@@ -60,11 +60,17 @@ struct OperandLoader {
   static constexpr int kSlots = BMN * BK / 4 / NT;
   static_assert(BMN * BK % (4 * NT) == 0, "tile must split evenly into float4 slots");
 
+  // Slot -> (non-contracted index, k) of the first of its four elements.
+  //   MN-major: consecutive lanes run along mn (one k row per BMN/4 lanes).
+  //   K-major : a wave covers 16 mn x 16 k (four lanes per 64-byte row piece), further waves /
+  //             slots step through the other 16-wide k chunks and mn ranges.  With the +4 row
+  //             padding the four transposing LDS stores of such a wave fall on distinct banks.
   __device__ __forceinline__ static void coords(int slot, int tid, int& mn, int& k) {
     int v = tid + slot * NT;
     if (KMAJOR) {
-      k = (v % (BK / 4)) * 4;
-      mn = v / (BK / 4);
+      const int l = v & 63, chunk = v >> 6;
+      k = (chunk % (BK / 16)) * 16 + (l & 3) * 4;
+      mn = (chunk / (BK / 16)) * 16 + (l >> 2);
     } else {
       mn = (v % (BMN / 4)) * 4;
       k = v / (BMN / 4);
@@ -162,15 +168,15 @@ __device__ __forceinline__ void lds_read_frag(float (&dst)[F], const float* src)
   }
 }
 
-// work-groups per CU the register allocation is held to: two for the mid-size tiles (their
-// accumulators fit twice into the 512-register file), one for the 256 x 256 four-wave tile
+// waves per SIMD the register allocation is held to (second __launch_bounds__ argument): two
+// unless one wave's accumulators alone need more than half of the 512-register file
 template <int BM, int BN, int WGM, int WGN>
-constexpr int min_blocks_per_cu() {
+constexpr int min_waves_per_simd() {
   return (BM * BN / (WGM * WGN) > 128 * 64) ? 1 : 2;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool TA, bool TB>
-__global__ __launch_bounds__(64 * WGM * WGN, (min_blocks_per_cu<BM, BN, WGM, WGN>()))
+__global__ __launch_bounds__(64 * WGM * WGN, (min_waves_per_simd<BM, BN, WGM, WGN>()))
 void tiled_kernel(TiledParams p) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -227,14 +233,30 @@ void tiled_kernel(TiledParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[c][b][r] = 0.f;
 
-  floatx4 ra[LoadA::kSlots], rb[LoadB::kSlots];
+  // Small wave tiles (at most four MFMA blocks) prefetch two K steps ahead through two register
+  // sets per operand: while step t runs on LDS stage t & 1, the tile of step t+1 sits in set
+  // (t+1) & 1 (loaded during step t-1) and the loads of step t+2 go to set t & 1.  Two steps of
+  // matrix work then cover the global-memory latency, which keeps shapes with only one or two
+  // work-groups per CU from being latency-bound.  Large wave tiles have a whole step of 8 x 8+ MFMAs
+  // to hide behind and no registers to spare: one set, one step ahead.
+  constexpr int NS = (FM * FN <= 4) ? 2 : 1;
+  floatx4 ra[NS][LoadA::kSlots], rb[NS][LoadB::kSlots];
+
+  auto load_guarded = [&](int ti, floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots])
+                          __attribute__((always_inline)) {
+    if (ti < n_steps) {
+      const int k0 = k_begin + ti * BK;
+      const bool kfull = (k0 + BK <= k_end);
+      LoadA::load(qa, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, tid);
+      LoadB::load(qb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, tid);
+    }
+  };
 
   if (n_steps > 0) {
-    const bool kfull = (k_begin + BK <= k_end);
-    LoadA::load(ra, p.A, p.lda, m0, k_begin, p.M, k_end, a_full && kfull, tid);
-    LoadB::load(rb, p.B, p.ldb, n0, k_begin, p.N, k_end, b_full && kfull, tid);
-    LoadA::store(ra, As, tid);
-    LoadB::store(rb, Bs, tid);
+    load_guarded(0, ra[0], rb[0]);
+    LoadA::store(ra[0], As, tid);
+    LoadB::store(rb[0], Bs, tid);
+    if constexpr (NS == 2) load_guarded(1, ra[1], rb[1]);
   }
   __syncthreads();
 
@@ -244,11 +266,12 @@ void tiled_kernel(TiledParams p) {
   // One K step on LDS stage BUF.  Schedule (pinned with scheduling barriers):
   //   - operand registers are double-buffered: the LDS reads of sub-step kk+2 are issued before
   //     the MFMAs of sub-step kk, so their latency hides behind FM*FN matrix instructions;
-  //   - the global loads of the next K step are issued once the first block of MFMAs is queued;
-  //   - their LDS stores (other stage) are issued in front of the last block of MFMAs, so the
-  //     matrix pipe still has work while the wave writes LDS and reaches the barrier.
-  // `load_next` issues the loads, `have_next` says whether there is anything to store.
-  auto k_step = [&](auto buf_tag, auto&& load_next, bool have_next) __attribute__((always_inline)) {
+  //   - the global loads of the step after next are issued once the first block of MFMAs is queued;
+  //   - the LDS stores of the next step (other stage, other register set) are issued in front of
+  //     the last block of MFMAs, so the matrix pipe still has work while the wave writes LDS and
+  //     reaches the barrier.
+  // `load_ahead(set_a, set_b)` issues the loads, `have_next` says whether there is anything to store.
+  auto k_step = [&](auto buf_tag, auto&& load_ahead, bool have_next) __attribute__((always_inline)) {
     constexpr int BUF = decltype(buf_tag)::value;
     const float* a_s = a_rd + BUF * A_STAGE;
     const float* b_s = b_rd + BUF * B_STAGE;
@@ -262,10 +285,11 @@ void tiled_kernel(TiledParams p) {
         lds_read_frag<FM>(af[cur ^ 1], a_s + (kk + 2) * LDA_S);
         lds_read_frag<FN>(bf[cur ^ 1], b_s + (kk + 2) * LDB_S);
       }
-      if (kk == 2) load_next();
+      constexpr int LS = (NS == 2) ? BUF : 0, SS = (NS == 2) ? (BUF ^ 1) : 0;  // load-target / store-source set
+      if (kk == 2) load_ahead(ra[LS], rb[LS]);
       if (kk == BK - 2 && have_next) {
-        LoadA::store(ra, As + (BUF ^ 1) * A_STAGE, tid);
-        LoadB::store(rb, Bs + (BUF ^ 1) * B_STAGE, tid);
+        LoadA::store(ra[SS], As + (BUF ^ 1) * A_STAGE, tid);
+        LoadB::store(rb[SS], Bs + (BUF ^ 1) * B_STAGE, tid);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -281,40 +305,34 @@ void tiled_kernel(TiledParams p) {
   using Buf1 = std::integral_constant<int, 1>;
 
   int t = 0;
-  // ---- interior tiles: K steps whose successor is a full, aligned tile use the lean loads
+  // ---- interior tiles: K steps whose second successor is a full, aligned tile use the lean loads
   const int n_full = (a_full && b_full && LoadA::offsets_fit(p.lda) && LoadB::offsets_fit(p.ldb))
                          ? (k_end - k_begin) / BK : 0;
-  if (n_full > 2) {
+  if (n_full > NS + 1) {
     uint32_t offa[LoadA::kSlots], offb[LoadB::kSlots];
     LoadA::fast_offsets(offa, p.lda, tid);
     LoadB::fast_offsets(offb, p.ldb, tid);
-    const char* pa = LoadA::fast_base(p.A, p.lda, m0, k_begin + BK);
-    const char* pb = LoadB::fast_base(p.B, p.ldb, n0, k_begin + BK);
+    const char* pa = LoadA::fast_base(p.A, p.lda, m0, k_begin + NS * BK);
+    const char* pb = LoadB::fast_base(p.B, p.ldb, n0, k_begin + NS * BK);
     const int64_t sa = LoadA::fast_stride(p.lda), sb = LoadB::fast_stride(p.ldb);
-    auto lean = [&]() __attribute__((always_inline)) {
-      LoadA::fast_load(ra, pa, offa);
-      LoadB::fast_load(rb, pb, offb);
+    auto lean = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots]) __attribute__((always_inline)) {
+      LoadA::fast_load(qa, pa, offa);
+      LoadB::fast_load(qb, pb, offb);
       pa += sa;
       pb += sb;
     };
-    for (; t + 2 < n_full; t += 2) {  // loads tiles t+1 and t+2, both full
+    for (; t + NS + 1 < n_full; t += 2) {  // loads tiles t+NS and t+NS+1, both full
       k_step(Buf0{}, lean, true);
       k_step(Buf1{}, lean, true);
     }
   }
   // ---- everything else (edge tiles, unaligned operands, the K tail): guarded loads
   for (; t < n_steps; ++t) {
-    const bool more = (t + 1 < n_steps);
-    auto guarded = [&]() __attribute__((always_inline)) {
-      if (more) {
-        const int k0 = k_begin + (t + 1) * BK;
-        const bool kfull = (k0 + BK <= k_end);
-        LoadA::load(ra, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, tid);
-        LoadB::load(rb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, tid);
-      }
+    auto guarded = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots]) __attribute__((always_inline)) {
+      load_guarded(t + NS, qa, qb);
     };
-    if (t & 1) k_step(Buf1{}, guarded, more);
-    else k_step(Buf0{}, guarded, more);
+    if (t & 1) k_step(Buf1{}, guarded, t + 1 < n_steps);
+    else k_step(Buf0{}, guarded, t + 1 < n_steps);
   }
 
   // ---- epilogue

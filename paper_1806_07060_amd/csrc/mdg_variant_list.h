@@ -22,20 +22,19 @@
 // Tiled matrix-core kernel: work-group tile BM x BN x BK, WGM x WGN waves.
 //   X(cfg, BM, BN, BK, WGM, WGN)
 #define MDG_TILED_CONFIGS(X)   \
-  X(0, 256, 256, 16, 2, 2)     \
-  X(1, 256, 256, 16, 2, 4)     \
-  X(2, 256, 128, 16, 2, 2)     \
-  X(3, 128, 256, 16, 2, 2)     \
-  X(4, 128, 128, 16, 2, 2)     \
-  X(5, 128, 128, 32, 2, 2)     \
-  X(6, 128, 64, 16, 2, 2)      \
-  X(7, 64, 128, 16, 2, 2)      \
-  X(8, 64, 64, 16, 2, 2)       \
-  X(9, 64, 64, 32, 2, 2)       \
-  X(10, 32, 32, 32, 1, 1)      \
-  X(11, 256, 256, 32, 2, 4)     \
-  X(12, 128, 32, 32, 4, 1)      \
-  X(13, 32, 128, 32, 1, 4)
+  X(0, 256, 256, 16, 2, 4)     \
+  X(1, 256, 128, 16, 2, 2)     \
+  X(2, 128, 256, 16, 2, 2)     \
+  X(3, 128, 128, 16, 2, 2)     \
+  X(4, 128, 128, 32, 2, 2)     \
+  X(5, 128, 64, 16, 2, 2)      \
+  X(6, 64, 128, 16, 2, 2)      \
+  X(7, 64, 64, 16, 2, 2)       \
+  X(8, 64, 64, 32, 2, 2)       \
+  X(9, 32, 32, 32, 1, 1)      \
+  X(10, 256, 256, 32, 2, 4)     \
+  X(11, 128, 32, 32, 4, 1)      \
+  X(12, 32, 128, 32, 1, 4)
 
 // Skinny-N kernel: streams A once; NB columns of C are held per thread.
 //   X(cfg, NB)
@@ -65,30 +64,31 @@
   V(TILED, 6, 1)        \
   V(TILED, 7, 1)        \
   V(TILED, 8, 1)        \
-  V(TILED, 9, 1)        \
+  V(TILED, 9, 1)       \
   V(TILED, 10, 1)       \
   V(TILED, 11, 1)       \
   V(TILED, 12, 1)       \
-  V(TILED, 13, 1)       \
-  V(TILED, 2, 2)        \
-  V(TILED, 4, 2)        \
-  V(TILED, 4, 4)        \
-  V(TILED, 4, 8)        \
-  V(TILED, 8, 2)        \
-  V(TILED, 8, 4)        \
-  V(TILED, 8, 8)        \
-  V(TILED, 8, 16)       \
-  V(TILED, 10, 4)       \
-  V(TILED, 10, 16)      \
-  V(TILED, 10, 64)      \
-  V(TILED, 6, 2)        \
-  V(TILED, 6, 4)        \
+  V(TILED, 1, 2)        \
+  V(TILED, 3, 2)        \
+  V(TILED, 3, 4)        \
+  V(TILED, 3, 8)        \
   V(TILED, 7, 2)        \
   V(TILED, 7, 4)        \
+  V(TILED, 7, 8)        \
+  V(TILED, 7, 16)       \
+  V(TILED, 9, 4)       \
+  V(TILED, 9, 16)      \
+  V(TILED, 9, 64)      \
+  V(TILED, 5, 2)        \
+  V(TILED, 5, 4)        \
+  V(TILED, 6, 2)        \
+  V(TILED, 6, 4)        \
+  V(TILED, 11, 4)       \
+  V(TILED, 11, 16)      \
   V(TILED, 12, 4)       \
   V(TILED, 12, 16)      \
-  V(TILED, 13, 4)       \
-  V(TILED, 13, 16)      \
+  V(TILED, 8, 2)        \
+  V(TILED, 8, 4)        \
   V(SKINNY, 0, 1)       \
   V(SKINNY, 1, 1)       \
   V(SKINNY, 2, 1)       \

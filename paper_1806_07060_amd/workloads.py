@@ -274,6 +274,21 @@ def config_wide(n_shapes=1000, max_flops=2 ** 38, max_bytes=1.5e9, max_operand_b
     return _dress(triples, 7, "wide")
 
 
+def config_big(n_shapes=200, max_flops=2 ** 41, max_bytes=1.5e9, max_operand_bytes=6e8):
+    """Large products: dimensions log-uniform in [512, 16384] under the same memory caps as the wide sweep and
+    2MNK <= max_flops.  Gives the selector training inputs in the range of the biggest square cases."""
+    rng = np.random.Generator(np.random.PCG64(case_seed(8, 0)))
+    triples = []
+    while len(triples) < n_shapes:
+        m, n, k = (int(round(512.0 * 2.0 ** (5.0 * rng.uniform()))) for _ in range(3))
+        if 2 * m * n * k > max_flops or 4 * (m * k + k * n + m * n) > max_bytes:
+            continue
+        if 4 * max(m * k, k * n, m * n) > max_operand_bytes:
+            continue
+        triples.append((m, n, k))
+    return _dress(triples, 8, "big")
+
+
 # ------------------------------------------------------------------------------------------
 # synthetic timing tables for selector tests (no GPU involved)
 # ------------------------------------------------------------------------------------------

@@ -195,3 +195,29 @@ def test_non_default_stream_and_repeatability():
         outs.append(dC.cpu().numpy())
     assert np.array_equal(outs[0], outs[1])  # deterministic: no atomics anywhere
     gu.check_against_oracle(case, outs[0], A, B, C0)
+
+
+def test_split_k_is_repeatable_and_exact():
+    # K slices are added in slice order by the reduce pass: many back-to-back calls on one stream
+    # (the workspace is re-used every time) must give bit-identical, oracle-exact results on integer data
+    gu = _gu()
+    torch = gu.torch_mod()
+    case = GemmCase(300, 200, 1100, NT, TR, 1.0, 0.0, dist="smallint", c0="zero", seed=wl.case_seed(14, 0),
+                    name="splitk-repeat").resolved()
+    A, B, C0 = wl.make_operands(case)
+    ref = gu.oracle_result(case, A, B, C0)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    stream = torch.cuda.current_stream().cuda_stream
+    for v in gu.legal_variants(case):
+        d = mdg.mdg_variant_info(v)
+        if d["family"] != mdg.FAMILY_TILED or d["split_k"] == 1:
+            continue
+        outs = [torch.from_numpy(C0).cuda() for _ in range(12)]
+        for dC in outs:  # no synchronisation in between
+            st = mdg.mdg_sgemm_variant(v, case.layout, case.transA, case.transB, case.M, case.N, case.K, case.alpha,
+                                       dA.data_ptr(), case.lda, dB.data_ptr(), case.ldb, case.beta, dC.data_ptr(),
+                                       case.ldc, stream)
+            assert st == 0
+        torch.cuda.synchronize()
+        for dC in outs:
+            assert np.array_equal(dC.cpu().numpy(), ref), d["name"]
