@@ -78,16 +78,24 @@ def time_variant(v, case, pools, n_sets, sa, sb, sc, stream, warmup, reps, spans
     return float(np.median(ms)) * 1e-3
 
 
-def measure_case(case, pools, stream, variants, span_ms=1.0, spans=3, prune=6.0, max_reps=200):
-    """Seconds of every variant on one column-major case (inf where illegal)."""
+def measure_case(case, pools, stream, variants, span_ms=1.0, spans=3, prune=6.0, max_reps=200, known=None):
+    """Seconds of every variant on one column-major case (inf where illegal).
+
+    `known` maps variant ids to times measured earlier (same protocol): those are kept, not re-measured.
+    """
     c = case.resolved()
     assert c.layout == wl.COL_MAJOR
     n_sets, sa, sb, sc = pools.layout(c)
     out = np.full(len(variants), np.inf)
     best = np.inf
+    for v, t in (known or {}).items():
+        out[v] = t
+        best = min(best, t)
     # likely-good variants first so that pruning bites early
     order = sorted(range(len(variants)), key=lambda v: (variants[v]["family"] != mdg.FAMILY_TILED, v))
     for v in order:
+        if known is not None and v in known:
+            continue
         if mdg.mdg_variant_legal(v, c.tA(), c.tB(), c.M, c.N, c.K, c.lda, c.ldb, c.ldc, pools.A.data_ptr(),
                                  pools.B.data_ptr(), pools.C.data_ptr()) != 1:
             continue
@@ -146,6 +154,9 @@ def main(argv=None):
     ap.add_argument("--span-ms", type=float, default=1.0)
     ap.add_argument("--spans", type=int, default=3)
     ap.add_argument("--prune", type=float, default=6.0)
+    ap.add_argument("--extend-from", default=None, metavar="CSV",
+                    help="a table of the same inputs written for an older variant table: times of variants it "
+                         "already holds (matched by name) are copied, only the new variants are measured")
     args = ap.parse_args(argv)
 
     import torch
@@ -163,6 +174,11 @@ def main(argv=None):
     want_header = ["index", "name", "M", "N", "K", "tA", "tB", "alpha", "beta"] + [v["name"] for v in variants]
     if header is not None and header != want_header:
         raise SystemExit(f"{args.out} was written for a different variant table; move it away first")
+    old_rows, old_names = {}, []
+    if args.extend_from:
+        old_header, old_rows = load_done(args.extend_from)
+        old_names = old_header[9:]
+        name_to_id = {v["name"]: v["id"] for v in variants}
     t0 = time.time()
     with open(args.out, "a", newline="") as f:
         w = csv.writer(f)
@@ -174,7 +190,12 @@ def main(argv=None):
                 continue
             if time.time() - t0 > args.budget_s:
                 break
-            times = measure_case(c, pools, stream, variants, args.span_ms, args.spans, args.prune)
+            known = None
+            if i in old_rows:
+                r = old_rows[i]
+                assert (int(r[2]), int(r[3]), int(r[4]), int(r[5]), int(r[6])) == (c.M, c.N, c.K, c.tA(), c.tB()), r[:7]
+                known = {name_to_id[n]: float(x) for n, x in zip(old_names, r[9:]) if n in name_to_id}
+            times = measure_case(c, pools, stream, variants, args.span_ms, args.spans, args.prune, known=known)
             w.writerow([i, c.name, c.M, c.N, c.K, c.tA(), c.tB(), repr(c.alpha), repr(c.beta)] +
                        [repr(float(t)) for t in times])
             f.flush()

@@ -139,3 +139,33 @@ def test_shipped_selector_matches_the_stored_model():
     d = model["default_dispatch"]
     assert mdg.mdg_select_default(0, 0, 4096, 4096, 4096) == d["tiled"]
     assert mdg.mdg_select_default(0, 0, 8, 8, 8) == d["direct"]
+
+
+def test_training_union_keeps_evaluation_shapes_out_and_is_seeded():
+    from paper_1806_07060_amd.tuning import train
+    X4, T4, _, _ = _table(100, 5, 21)
+    Xe, Te, _, _ = _table(40, 5, 22)
+    tab4 = {"X": X4, "T": T4}
+    extra = {"X": np.vstack([Xe, X4[90:95]]), "T": np.vstack([Te, T4[90:95]])}
+    banned = {"X": Xe[:7], "T": Te[:7]}
+    X, T, src = train.training_union(tab4, [("grid", extra)], [banned])
+    # 80 rows of the sweep + 45 extra rows minus the 7 banned shapes
+    assert X.shape[0] == 80 + 45 - 7 and src.count("cfg4") == 80 and src.count("grid") == 38
+    have = {tuple(r[:3]) for r in X.tolist()}
+    assert not ({tuple(r[:3]) for r in Xe[:7].tolist()} & have)
+    # the held-out 20 % of the sweep never enters through the sweep itself
+    assert {tuple(r) for r in X[[i for i, s in enumerate(src) if s == "cfg4"]].tolist()} == {tuple(r) for r in X4[:80].tolist()}
+    X2, T2, src2 = train.training_union(tab4, [("grid", extra)], [banned])
+    assert np.array_equal(X, X2) and np.array_equal(T, T2) and src == src2
+
+
+def test_default_dispatch_picks_per_family_bests_on_the_two_cubes():
+    from paper_1806_07060_amd.tuning import train
+    meta = [{"family": 0, "split_k": 1}, {"family": 0, "split_k": 1}, {"family": 1, "split_k": 1},
+            {"family": 1, "split_k": 1}, {"family": 1, "split_k": 4}]
+    X = np.array([[256, 256, 256, a, b] for a in (0, 1) for b in (0, 1)] + [[1024, 1024, 1024, a, b] for a in (0, 1) for b in (0, 1)])
+    T = np.ones((8, 5))
+    T[:4] = [2.0, 1.5, 1.0, 3.0, 0.5]  # 256-cube: best direct is variant 1 (tiled ones do not count)
+    T[4:] = [9.0, 9.0, 4.0, 3.0, 1.0]  # 1024-cube: best tiled without split-K is variant 3
+    tiled, direct, thr = train.default_dispatch({"X": X, "T": T}, meta)
+    assert (tiled, direct, thr) == (3, 1, 512.0 ** 3)
