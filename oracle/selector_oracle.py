@@ -30,7 +30,12 @@ Readings where the paper is silent or ambiguous:
   - besides the arithmetic mean (the paper's DTPR) the geometric mean is reported;
   - leaf labels: 'majority' (plain CART) or 'logratio' (the variant maximising
     the summed log performance ratio of the leaf's training inputs -- uses the
-    whole table; answers the misclassification-cost issue raised in Section 5.2).
+    whole table; answers the misclassification-cost issue raised in Section 5.2);
+  - 'regret' (an extension in the direction of the paper's future work, not in
+    the paper): integer costs c[s][v] = round(-2^20 * log(performance ratio)),
+    cost of a node = min over v of the column sum over its inputs, a split
+    minimises the summed cost of its children (ties: lowest feature, lowest
+    threshold), a node of cost 0 is a leaf, the label is the minimising variant.
 
 All split comparisons are done in exact rational arithmetic, so the tree is a
 pure function of the data and the rules above.
@@ -118,6 +123,47 @@ def _best_split(X, y, idx, L_abs):
     return best
 
 
+REGRET_SCALE = 2 ** 20
+
+
+def regret_cost_rows(rows, fallback=0):
+    """Integer cost of every (input, variant): round(-2^20 * log(f_v / f_best)), fallback-priced."""
+    return [[round(-math.log(performance_ratio(r, v, fallback)) * REGRET_SCALE) for v in range(len(r))] for r in rows]
+
+
+def _node_cost(cost, idx):
+    n_var = len(cost[0])
+    return min(sum(cost[s][v] for s in idx) for v in range(n_var))
+
+
+def _node_label_regret(cost, idx):
+    n_var = len(cost[0])
+    sums = [sum(cost[s][v] for s in idx) for v in range(n_var)]
+    return sums.index(min(sums))
+
+
+def _best_split_regret(X, cost, idx, L_abs):
+    """Lowest  cost(left) + cost(right)  over all (feature, threshold); None if no split is allowed."""
+    n, n_var = len(idx), len(cost[0])
+    best = None  # (score, feature, threshold)
+    for f in range(len(X[0])):
+        order = sorted(idx, key=lambda s: X[s][f])
+        left = [0] * n_var
+        right = [sum(cost[s][v] for s in order) for v in range(n_var)]
+        for pos in range(n - 1):
+            s = order[pos]
+            for v in range(n_var):
+                left[v] += cost[s][v]
+                right[v] -= cost[s][v]
+            a, b = X[s][f], X[order[pos + 1]][f]
+            if a == b or pos + 1 < L_abs or n - pos - 1 < L_abs:
+                continue
+            score = min(left) + min(right)
+            if best is None or score < best[0]:
+                best = (score, f, (a + b) // 2)
+    return best
+
+
 def fit_cart(X, y, H=None, L=1, leaf_rule="majority", table=None, fallback=0):
     """Grow the tree. X: list of integer feature tuples, y: list of labels.
 
@@ -126,19 +172,25 @@ def fit_cart(X, y, H=None, L=1, leaf_rule="majority", table=None, fallback=0):
     Returns nested dicts: {'feature', 'threshold', 'left', 'right', 'n'} or {'leaf': label, 'n': samples}.
     """
     L_abs = min_samples_leaf(L, len(X))
+    cost = regret_cost_rows(table, fallback) if leaf_rule == "regret" else None
 
     def leaf(idx):
         if leaf_rule == "majority":
             lab = _majority([y[s] for s in idx])
+        elif leaf_rule == "regret":
+            lab = _node_label_regret(cost, idx)
         else:
             lab = logratio_label([table[s] for s in idx], fallback)
         return {"leaf": lab, "n": len(idx)}
 
     def grow(idx, depth):
-        labs = set(y[s] for s in idx)
-        if len(labs) == 1 or (H is not None and depth >= H) or len(idx) < 2 * L_abs:
+        if leaf_rule == "regret":
+            pure = _node_cost(cost, idx) == 0
+        else:
+            pure = len(set(y[s] for s in idx)) == 1
+        if pure or (H is not None and depth >= H) or len(idx) < 2 * L_abs:
             return leaf(idx)
-        sp = _best_split(X, y, idx, L_abs)
+        sp = _best_split_regret(X, cost, idx, L_abs) if leaf_rule == "regret" else _best_split(X, y, idx, L_abs)
         if sp is None:
             return leaf(idx)
         _, f, thr = sp

@@ -21,6 +21,14 @@ Leaf labels: 'majority' (plain CART) or 'logratio' (the variant maximising the
 summed log performance ratio over the leaf's training inputs, which prices a
 misclassification by what it costs -- the weakness Section 5.2 points out for
 accuracy-driven trees).
+
+A third rule, 'regret', also makes the *splits* cost-sensitive (one of the
+"more effective models" the paper's conclusion asks for): every (input,
+variant) pair gets an integer cost round(-2^20 * log(f_variant / f_best)), a
+node's cost is the smallest column sum over its inputs (the loss of the best
+single variant for that node), and a split is chosen to minimise the summed
+cost of its two children.  Integer costs keep every comparison exact.  A node
+whose cost is zero is not split; its label is the minimising variant.
 """
 from fractions import Fraction
 import math
@@ -72,6 +80,15 @@ def geomean_ratio(times, pred, fallback=0):
 
 def accuracy(pred, labels):
     return float(np.mean(np.asarray(pred) == np.asarray(labels)))
+
+
+REGRET_SCALE = 1 << 20
+
+
+def regret_costs(times, fallback=0):
+    """Integer cost of running variant v on input s: round(-2^20 * log(t_best / t_v)), fallback-priced."""
+    T = np.asarray(times, dtype=np.float64)
+    return np.rint(-np.log(T.min(axis=1, keepdims=True) / effective_times(T, fallback)) * REGRET_SCALE).astype(np.int64)
 
 
 class Tree:
@@ -149,6 +166,30 @@ def _best_split(X, y_idx, idx, n_classes, L_abs):
     return None if best is None else (best[1], best[2])
 
 
+def _best_split_regret(X, cost, idx, L_abs):
+    """(feature, threshold) minimising  min_v sum_left cost + min_v sum_right cost  (exact integers), or None."""
+    n = idx.size
+    best = None  # (score, feature, threshold)
+    for f in range(X.shape[1]):
+        xs = X[idx, f]
+        order = np.argsort(xs, kind="stable")
+        xs = xs[order]
+        C = cost[idx][order]
+        P = np.cumsum(C, axis=0)
+        tot = P[-1]
+        P = P[:-1]
+        nL = np.arange(1, n, dtype=np.int64)
+        valid = (xs[:-1] != xs[1:]) & (nL >= L_abs) & (n - nL >= L_abs)
+        if not valid.any():
+            continue
+        score = P.min(axis=1) + (tot - P).min(axis=1)
+        score[~valid] = np.iinfo(np.int64).max
+        pos = int(np.argmin(score))  # first minimum = lowest threshold
+        if best is None or score[pos] < best[0]:
+            best = (int(score[pos]), f, (int(xs[pos]) + int(xs[pos + 1])) // 2)
+    return None if best is None else (best[1], best[2])
+
+
 def fit_cart(X, times, H=None, L=1, leaf_rule="majority", fallback=0, labels=None):
     """Grow a tree on features X [n, 5] and the timing table `times` [n, V]."""
     X = np.asarray(X, dtype=np.int64)
@@ -159,20 +200,27 @@ def fit_cart(X, times, H=None, L=1, leaf_rule="majority", fallback=0, labels=Non
     logr = None
     if leaf_rule == "logratio":
         logr = np.log(T.min(axis=1, keepdims=True) / effective_times(T, fallback))
+    cost = regret_costs(T, fallback) if leaf_rule == "regret" else None
     tree = Tree()
 
     def leaf_label(idx):
         if leaf_rule == "majority":
             cnt = np.bincount(y_idx[idx], minlength=classes.size)
             return int(classes[np.argmax(cnt)])  # first maximum = lowest id
+        if leaf_rule == "regret":
+            return int(np.argmin(np.sum(cost[idx], axis=0)))  # first minimum = lowest id
         return int(np.argmax(np.sum(logr[idx], axis=0)))
 
     def grow(idx, depth):
         node = tree._new(int(idx.size))
-        pure = np.all(y_idx[idx] == y_idx[idx[0]])
+        if leaf_rule == "regret":
+            pure = int(np.sum(cost[idx], axis=0).min()) == 0
+        else:
+            pure = np.all(y_idx[idx] == y_idx[idx[0]])
         sp = None
         if not pure and (H is None or depth < H) and idx.size >= 2 * L_abs:
-            sp = _best_split(X, y_idx, idx, classes.size, L_abs)
+            sp = (_best_split_regret(X, cost, idx, L_abs) if leaf_rule == "regret"
+                  else _best_split(X, y_idx, idx, classes.size, L_abs))
         if sp is None:
             tree.label[node] = leaf_label(idx)
             return node
@@ -218,7 +266,8 @@ def cross_validate(X, T, H, L, leaf_rule, fallback=0, folds=5):
     return float(np.exp(np.mean(np.concatenate(logs))))
 
 
-def select_model(X_train, T_train, fallback=0, folds=5, H_set=H_SET, L_set=L_SET, leaf_rules=("majority", "logratio")):
+def select_model(X_train, T_train, fallback=0, folds=5, H_set=H_SET, L_set=L_SET,
+                 leaf_rules=("majority", "logratio", "regret")):
     """Choose (H, L, leaf rule) by cross-validation inside the training set; the held-out set is not touched."""
     table = []
     for rule in leaf_rules:

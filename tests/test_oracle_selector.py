@@ -225,3 +225,45 @@ def test_logratio_leaf_label_by_hand():
     assert so.logratio_label([[math.inf, 2.0], [1.0, 3.0]], fallback=1) == 0
     t = so.fit_cart([(1,), (2,), (3,)], [0, 0, 1], H=0, leaf_rule="logratio", table=rows)
     assert t == {"leaf": 1, "n": 3}
+
+
+def test_regret_tree_by_hand():
+    # two variants; costs in units of log-ratio.  Inputs 1..4 on one feature:
+    #   x=1,2: variant 0 is best (variant 1 twice as slow);  x=3: variant 1 best (variant 0 4x slower);
+    #   x=4: variant 1 best (variant 0 only 1 % slower).
+    X = [(1,), (2,), (3,), (4,)]
+    T = [[1.0, 2.0], [1.0, 2.0], [4.0, 1.0], [1.01, 1.0]]
+    y = so.labels_from_table(T)
+    cost = so.regret_cost_rows(T)
+    assert cost[0] == [0, round(math.log(2) * 2 ** 20)] and cost[2] == [round(math.log(4) * 2 ** 20), 0]
+    # depth-0 tree: variant 0 costs log4 + log1.01, variant 1 costs 2 log2 = log4 -> variant 1
+    assert so.fit_cart(X, y, H=0, leaf_rule="regret", table=T) == {"leaf": 1, "n": 4}
+    # the cut after x=2 leaves both sides with a zero-cost variant: it must be chosen
+    t = so.fit_cart(X, y, H=1, leaf_rule="regret", table=T)
+    assert (t["feature"], t["threshold"]) == (0, 2) and t["left"]["leaf"] == 0 and t["right"]["leaf"] == 1
+    # Gini sees the same labels here; make x=4 prefer variant 0 by a hair: Gini now wants {1,2},{3},{4} (3 leaves),
+    # the regret tree with L=2 must keep {3,4} together and label it 1 (the hair costs less than the factor 4)
+    T2 = [[1.0, 2.0], [1.0, 2.0], [4.0, 1.0], [1.0, 1.01]]
+    t2 = so.fit_cart(X, so.labels_from_table(T2), L=2, leaf_rule="regret", table=T2)
+    assert t2["threshold"] == 2 and t2["right"] == {"leaf": 1, "n": 2}
+    # a node whose best single variant already costs nothing is not split, whatever the labels say
+    T3 = [[1.0, 1.0], [1.0, 2.0], [1.0, 1.0], [1.0, 3.0]]
+    assert so.fit_cart(X, [1, 0, 1, 0], leaf_rule="regret", table=T3) == {"leaf": 0, "n": 4}
+
+
+def test_regret_trees_never_score_below_their_own_root_and_respect_limits():
+    X, T = _table(200, 8, 13)
+    y = so.labels_from_table(T)
+    root = so.fit_cart(X, y, H=0, leaf_rule="regret", table=T)
+    base = so.geomean_ratio(T, [root["leaf"]] * len(X))
+    for H, L in ((2, 1), (4, 5), (None, 10), (None, 0.2)):
+        tree = so.fit_cart(X, y, H, L, "regret", T)
+        st = so.tree_stats(tree)
+        assert st["min_leaf_samples"] >= so.min_samples_leaf(L, len(X))
+        if H is not None:
+            assert st["height"] <= H
+        pred = [so.predict(tree, x) for x in X]
+        # every split lowers (or keeps) the summed training cost, so the training geomean cannot get worse
+        assert so.geomean_ratio(T, pred) >= base - 1e-12
+    full = so.fit_cart(X, y, None, 1, "regret", T)
+    assert so.geomean_ratio(T, [so.predict(full, x) for x in X]) == 1.0  # distinct inputs -> zero training cost

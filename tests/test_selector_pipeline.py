@@ -28,7 +28,7 @@ def test_labels_and_trees_are_identical_to_the_oracle(seed, n, v):
     X, T, Xl, Tl = _table(n, v, seed)
     assert cart.labels_from_table(T).tolist() == so.labels_from_table(Tl)
     y = so.labels_from_table(Tl)
-    for rule in ("majority", "logratio"):
+    for rule in ("majority", "logratio", "regret"):
         for H, L in ((1, 1), (2, 4), (4, 0.1), (8, 2), (None, 1), (None, 4), (None, 0.3), (3, 0.5)):
             ours = cart.fit_cart(X, T, H, L, rule).to_nested()
             ref = so.fit_cart(Xl, y, H, L, rule, Tl, 0)
@@ -38,7 +38,7 @@ def test_labels_and_trees_are_identical_to_the_oracle(seed, n, v):
 def test_predictions_and_metrics_match_the_oracle():
     X, T, Xl, Tl = _table(300, 10, 3)
     tr, te = slice(0, 240), slice(240, 300)
-    for rule in ("majority", "logratio"):
+    for rule in ("majority", "logratio", "regret"):
         ours = cart.sweep(X[tr], T[tr], X[te], T[te], leaf_rule=rule)
         ref = so.sweep(Xl[tr], Tl[tr], Xl[te], Tl[te], leaf_rule=rule)
         assert [r["name"] for r in ours] == [r["name"] for r in ref]
@@ -68,7 +68,7 @@ def test_illegal_predictions_are_priced_as_the_fallback():
 def test_cross_validation_selects_a_model_without_the_heldout_set():
     X, T, _, _ = _table(250, 9, 4)
     best, table = cart.select_model(X[:200], T[:200], folds=4, H_set=(2, None), L_set=(1, 4, 0.2))
-    assert len(table) == 12 and best in table
+    assert len(table) == 18 and best in table  # 2 heights x 3 leaf sizes x 3 rules
     assert all(0 < r["cv_geomean"] <= 1 for r in table)
     assert best["cv_geomean"] == max(r["cv_geomean"] for r in table)
 
