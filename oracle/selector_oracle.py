@@ -8,7 +8,9 @@ Section 4.2; metrics of Section 5.2), step by step and in the paper's notation:
                    (+inf where v cannot run on s); FLOPS f = 2 M N K / T
   a-bar(s)         argmax_a f_a(s): the best variant of each input (the label)
   X, Y             first 80 % / last 20 % of the (already shuffled) inputs
-  CART             binary decision tree on the integer features I = (M, N, K, tA, tB)
+  CART             binary decision tree on integer features of I = (M, N, K, tA, tB):
+                   the raw values plus M*N and M*N*K (expand_features; the paper uses
+                   the raw triple only -- the products are this build's addition)
                    grown with the Gini impurity, limited by H (maximum height,
                    None = unlimited) and L (minimum samples per leaf: an integer,
                    or a fraction in (0, 1) of the training samples)
@@ -48,7 +50,15 @@ most frequent label, and scikit-learn's CART where no ties occur.
 from fractions import Fraction
 import math
 
-FEATURE_NAMES = ("M", "N", "K", "tA", "tB")
+FEATURE_NAMES = ("M", "N", "K", "tA", "tB", "MN", "MNK")
+INT64_MAX = 2 ** 63 - 1
+
+
+def expand_features(x):
+    """Input description (M, N, K, tA, tB) -> the seven tree features: the five raw values, the size of C
+    (M*N) and the work (M*N*K), the products saturating at 2^63 - 1 like the 64-bit code that evaluates the tree."""
+    M, N, K, tA, tB = x
+    return (M, N, K, tA, tB, min(M * N, INT64_MAX), min(M * N * K, INT64_MAX))
 
 
 # ----- labelling ---------------------------------------------------------------------------

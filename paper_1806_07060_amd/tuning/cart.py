@@ -5,7 +5,9 @@ hyper-parameters H = maximum height and L = minimum samples per leaf) and
 Section 5.2 (accuracy and DTPR) of the paper:
 
   label(s)   = argmax_a f_a(s) = the variant with the smallest measured time
-  tree       = CART on the integer features (M, N, K, tA, tB), Gini impurity
+  tree       = CART on integer features of the input description (M, N, K, tA, tB):
+               the five raw values plus the two products M*N (size of C, i.e. how many
+               tiles there are to share among the CUs) and M*N*K (the work), Gini impurity
   DTPR       = mean over inputs of f_predicted / f_best
 
 Rules fixed where the paper leaves them open: fractional L = ceil(L * n)
@@ -35,7 +37,22 @@ import math
 
 import numpy as np
 
-FEATURES = ("M", "N", "K", "tA", "tB")
+RAW_FEATURES = ("M", "N", "K", "tA", "tB")
+FEATURES = RAW_FEATURES + ("MN", "MNK")
+INT64_MAX = (1 << 63) - 1
+
+
+def expand_features(X):
+    """[n, 5] raw (M, N, K, tA, tB) -> [n, 7] with M*N and M*N*K appended (saturating at INT64_MAX,
+    exactly as the generated C++ computes them).  Arrays that already have 7 columns pass through."""
+    X = np.asarray(X, dtype=np.int64).reshape(-1, np.asarray(X).shape[-1])
+    if X.shape[1] == len(FEATURES):
+        return X
+    assert X.shape[1] == len(RAW_FEATURES)
+    mn = [int(m) * int(n) for m, n in zip(X[:, 0].tolist(), X[:, 1].tolist())]  # Python ints: no overflow
+    mnk = [min(a * int(k), INT64_MAX) for a, k in zip(mn, X[:, 2].tolist())]
+    mn = [min(a, INT64_MAX) for a in mn]
+    return np.column_stack([X, np.array(mn, dtype=np.int64), np.array(mnk, dtype=np.int64)])
 H_SET = (1, 2, 4, 8, None)
 L_SET = (1, 2, 4, 0.1, 0.2, 0.3, 0.4, 0.5)
 
@@ -104,7 +121,7 @@ class Tree:
         return len(self.n) - 1
 
     def predict(self, X):
-        X = np.asarray(X, dtype=np.int64).reshape(-1, len(FEATURES))
+        X = expand_features(X)
         feature, threshold = np.array(self.feature), np.array(self.threshold)
         left, right, label = np.array(self.left), np.array(self.right), np.array(self.label)
         node = np.zeros(X.shape[0], dtype=np.int64)
@@ -191,8 +208,8 @@ def _best_split_regret(X, cost, idx, L_abs):
 
 
 def fit_cart(X, times, H=None, L=1, leaf_rule="majority", fallback=0, labels=None):
-    """Grow a tree on features X [n, 5] and the timing table `times` [n, V]."""
-    X = np.asarray(X, dtype=np.int64)
+    """Grow a tree on the inputs X [n, 5] (expanded to the 7 features) and the timing table `times` [n, V]."""
+    X = expand_features(X)
     T = np.asarray(times, dtype=np.float64)
     y = labels_from_table(T) if labels is None else np.asarray(labels, dtype=np.int64)
     classes, y_idx = np.unique(y, return_inverse=True)

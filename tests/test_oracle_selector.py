@@ -267,3 +267,12 @@ def test_regret_trees_never_score_below_their_own_root_and_respect_limits():
         assert so.geomean_ratio(T, pred) >= base - 1e-12
     full = so.fit_cart(X, y, None, 1, "regret", T)
     assert so.geomean_ratio(T, [so.predict(full, x) for x in X]) == 1.0  # distinct inputs -> zero training cost
+
+
+def test_expand_features_by_hand_and_saturation():
+    assert so.expand_features((3, 5, 7, 1, 0)) == (3, 5, 7, 1, 0, 15, 105)
+    assert so.expand_features((8192, 8192, 8192, 0, 1)) == (8192, 8192, 8192, 0, 1, 2 ** 26, 2 ** 39)
+    big = 2 ** 31 - 1
+    f = so.expand_features((big, big, big, 0, 0))
+    assert f[5] == big * big and f[6] == 2 ** 63 - 1  # M*N fits in 63 bits, M*N*K saturates
+    assert so.expand_features((0, 9, 9, 0, 0))[5:] == (0, 0)

@@ -20,7 +20,20 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _table(n, v, seed):
     feats, times = wl.synthetic_timing_table(n, v, seed)
-    return feats, times, [tuple(int(a) for a in r) for r in feats], [list(map(float, r)) for r in times]
+    # product side: raw [n, 5] inputs (it expands them itself); oracle side: tuples expanded by the oracle's own rule
+    return feats, times, [so.expand_features(tuple(int(a) for a in r)) for r in feats], [list(map(float, r)) for r in times]
+
+
+def _probe(feature, value, base=(64, 64, 64, 0, 1)):
+    """A raw input (M, N, K, tA, tB) whose tree feature `feature` equals `value` (products via N = K = 1)."""
+    p = list(base)
+    if feature < 5:
+        p[feature] = value
+    elif feature == 5:
+        p[0], p[1] = value, 1
+    else:
+        p[0], p[1], p[2] = value, 1, 1
+    return tuple(p)
 
 
 @pytest.mark.parametrize("seed,n,v", [(1, 200, 8), (2, 320, 14)])
@@ -98,20 +111,19 @@ def test_generated_cpp_equals_the_tree_everywhere(H, L, rule, tmp_path):
     assert lib.name() == b"test-model" and lib.dflt(0) == 3 and lib.dflt(1) == 1
     # all training shapes plus threshold-1 / threshold / threshold+1 probes of every internal node
     probes = [tuple(r) for r in X.tolist()]
-    base = X[0].tolist()
     for f, thr in codegen.internal_thresholds(nested):
         for d in (-1, 0, 1):
-            p = list(base)
-            p[f] = thr + d
-            probes.append(tuple(p))
-            q = [1, 1, 1, 0, 0]
-            q[f] = thr + d
-            probes.append(tuple(q))
+            probes.append(_probe(f, max(thr + d, 0), base=tuple(X[0].tolist())))
+            probes.append(_probe(f, max(thr + d, 0), base=(1, 1, 1, 0, 0)))
+    assert {f for f, _ in codegen.internal_thresholds(nested)} & {5, 6} or H == 0  # the products are used
     P = np.array(probes, dtype=np.int64)
     want = tree.predict(P)
     got = [lib.sel(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) for p in P]
     assert got == want.tolist()
-    assert got == [so.predict(nested, tuple(int(x) for x in p)) for p in P]
+    assert got == [so.predict(nested, so.expand_features(tuple(int(x) for x in p))) for p in P]
+    # saturation of the products: huge dimensions must not wrap around
+    big = (2 ** 31 - 1, 2 ** 31 - 1, 2 ** 31 - 1, 0, 0)
+    assert lib.sel(0, 0, big[0], big[1], big[2]) == so.predict(nested, so.expand_features(big)) == int(tree.predict([big])[0])
 
 
 def test_shipped_selector_matches_the_stored_model():
@@ -129,13 +141,11 @@ def test_shipped_selector_matches_the_stored_model():
     extra = []
     for f, thr in codegen.internal_thresholds(model["tree"]):
         for d in (-1, 0, 1):
-            p = [64, 64, 64, 0, 1]
-            p[f] = max(0, thr + d)
-            extra.append(p)
+            extra.append(_probe(f, max(0, thr + d)))
     P = np.vstack([P, np.array(extra, dtype=np.int64).reshape(-1, 5)])
     for p in P:
         assert mdg.mdg_select(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) == \
-            so.predict(model["tree"], tuple(int(x) for x in p))
+            so.predict(model["tree"], so.expand_features(tuple(int(x) for x in p)))
     d = model["default_dispatch"]
     assert mdg.mdg_select_default(0, 0, 4096, 4096, 4096) == d["tiled"]
     assert mdg.mdg_select_default(0, 0, 8, 8, 8) == d["direct"]
