@@ -171,9 +171,11 @@ def main():
     chosen = []
     for i, c in enumerate(cases):
         v = mdg.mdg_select(c.tA(), c.tB(), c.M, c.N, c.K)
-        if mdg.mdg_variant_legal(v, c.tA(), c.tB(), c.M, c.N, c.K, c.lda, c.ldb, c.ldc, dev[i][0].data_ptr(),
-                                 dev[i][1].data_ptr(), dev[i][2].data_ptr()) != 1:
-            v = 0
+        for _ in range(len(variants)):  # the dispatch's fallback chain
+            if v == 0 or mdg.mdg_variant_legal(v, c.tA(), c.tB(), c.M, c.N, c.K, c.lda, c.ldb, c.ldc,
+                                               dev[i][0].data_ptr(), dev[i][1].data_ptr(), dev[i][2].data_ptr()) == 1:
+                break
+            v = variants[v]["fallback"]
         chosen.append(v)
         sym = kernel_symbol(variants[v], c.tA(), c.tB())
         g = groups.setdefault(sym, {"ms": 0.0, "flops": 0.0, "launches": 0, "bytes": 0.0})

@@ -82,16 +82,18 @@ typedef struct {
   int32_t vec;         /* widest global access in fp32 elements */
   int32_t lds;         /* 1 if operands are staged through LDS */
   int32_t split_k;     /* number of K slices (1 = none); > 1 needs workspace and a reduce pass */
-  int32_t reserved;
+  int32_t fallback;    /* variant tried next when this one is not legal for an input (chains end at a variant that is) */
   char name[48];
 } mdg_variant_desc;
 
 /*
  * The GEMM call (Eq. 1, Section 2.2).  Validates, maps a row-major problem to
  * the equivalent column-major one (C^T = op(B)^T op(A)^T), asks the compiled
- * decision tree for a variant, replaces it by variant 0 if it is not legal for
- * this input (Section 4.1: every class must be a valid configuration for the
- * input), and enqueues the kernel(s) on `stream`.
+ * decision tree for a variant, and if that is not legal for this input
+ * (Section 4.1: every class must be a valid configuration for the input)
+ * follows the variant's fallback chain -- fewer K slices of the same tile, a
+ * wider skinny kernel, finally variant 0 -- to the first legal one, and
+ * enqueues the kernel(s) on `stream`.
  */
 int mdg_sgemm(int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha, const float* A,
               int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc, void* stream);

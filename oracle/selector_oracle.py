@@ -27,8 +27,9 @@ Readings where the paper is silent or ambiguous:
   - ties between equally good splits: lowest feature index, then lowest threshold
     (scikit-learn randomises; only behaviour, not structure, is comparable);
   - majority ties at a leaf: lowest variant id;
-  - a predicted variant that is illegal for an input is replaced by the
-    universal fallback variant, and the fallback's time is what the ratio sees;
+  - a predicted variant that is illegal for an input is replaced by a fallback
+    variant -- one universal variant, or per-variant links followed until a
+    legal variant is reached -- and the fallback's time is what the ratio sees;
   - besides the arithmetic mean (the paper's DTPR) the geometric mean is reported;
   - leaf labels: 'majority' (plain CART) or 'logratio' (the variant maximising
     the summed log performance ratio of the leaf's training inputs -- uses the
@@ -239,9 +240,19 @@ def tree_stats(tree):
 # ----- metrics -----------------------------------------------------------------------------
 
 def effective_time(times_row, v, fallback=0):
-    """Seconds the library would really spend when variant v is predicted (fallback if v is illegal)."""
-    t = times_row[v]
-    return t if math.isfinite(t) else times_row[fallback]
+    """Seconds the library would really spend when variant v is predicted.
+
+    `fallback` is one universal variant id, or a list of links (fallback[v] = the variant tried next when v is
+    illegal for the input): links are followed until a variant with a finite time is found.
+    """
+    if isinstance(fallback, int):
+        t = times_row[v]
+        return t if math.isfinite(t) else times_row[fallback]
+    for _ in range(len(times_row) + 1):
+        if math.isfinite(times_row[v]):
+            return times_row[v]
+        v = fallback[v]
+    raise ValueError("fallback links never reach a legal variant")
 
 
 def performance_ratio(times_row, v, fallback=0):

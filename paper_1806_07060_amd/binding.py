@@ -29,10 +29,10 @@ EXPORTS = ("mdg_sgemm", "mdg_sgemm_variant", "mdg_select", "mdg_select_default",
 
 class VariantDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("id", "family", "tile_m", "tile_n", "tile_k", "threads", "sub_m", "sub_n",
-                                              "vec", "lds", "split_k", "reserved")] + [("name", ctypes.c_char * 48)]
+                                              "vec", "lds", "split_k", "fallback")] + [("name", ctypes.c_char * 48)]
 
     def as_dict(self):
-        d = {n: int(getattr(self, n)) for n, _ in self._fields_[:-2]}
+        d = {n: int(getattr(self, n)) for n, _ in self._fields_[:-1]}
         d["name"] = self.name.decode()
         return d
 

@@ -73,10 +73,20 @@ def min_samples_leaf(L, n_train):
 
 
 def effective_times(times, fallback=0):
-    """Times with illegal entries (inf) replaced by the fallback variant's time of the same row."""
+    """Times the library really spends per predicted variant: illegal entries (inf) are replaced by the time of
+    the variant the dispatch falls back to.  `fallback` is either one universal variant id, or the library's
+    per-variant links (fallback[v] = variant tried next when v is illegal; chains end at a legal variant)."""
     T = np.asarray(times, dtype=np.float64)
-    fb = T[:, [fallback]]
-    return np.where(np.isfinite(T), T, fb)
+    if np.ndim(fallback) == 0:
+        return np.where(np.isfinite(T), T, T[:, [int(fallback)]])
+    link = np.asarray(fallback, dtype=np.int64)
+    E = T.copy()
+    for _ in range(T.shape[1]):  # every pass resolves at least one more hop of each chain
+        bad = ~np.isfinite(E)
+        if not bad.any():
+            break
+        E = np.where(bad, E[:, link], E)
+    return E
 
 
 def ratios(times, pred, fallback=0):

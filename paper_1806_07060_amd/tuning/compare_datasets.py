@@ -49,19 +49,21 @@ def main(folds=5):
     Xu, Tu, _ = training_union(tab4, list(extras.items()), excl)
     trainsets["union"] = (Xu, Tu)
 
+    from .. import binding as mdg
+    links = [int(v["fallback"]) for v in mdg.variants()]
     out = {}
     print(f"{'training set':20s} {'n':>5s} {'model':22s} " + " ".join(f"{k[:18]:>18s}" for k in tests))
     for name, (X, T) in trainsets.items():
-        best, _ = cart.select_model(X, T, folds=folds)
-        tree = cart.fit_cart(X, T, best["H"], best["L"], best["leaf_rule"])
+        best, _ = cart.select_model(X, T, fallback=links, folds=folds)
+        tree = cart.fit_cart(X, T, best["H"], best["L"], best["leaf_rule"], links)
         st = tree.stats()
         row = {"inputs": int(X.shape[0]), "model": f"{best['name']}/{best['leaf_rule']}", "cv_geomean": best["cv_geomean"],
                "leaves": st["leaves"], "height": st["height"], "scores": {}}
         cells = []
         for k, (Xt, Tt) in tests.items():
             pred = tree.predict(Xt)
-            sc = {"accuracy": cart.accuracy(pred, cart.labels_from_table(Tt)), "dtpr": cart.dtpr(Tt, pred),
-                  "geomean": cart.geomean_ratio(Tt, pred)}
+            sc = {"accuracy": cart.accuracy(pred, cart.labels_from_table(Tt)), "dtpr": cart.dtpr(Tt, pred, links),
+                  "geomean": cart.geomean_ratio(Tt, pred, links)}
             row["scores"][k] = sc
             cells.append(f"{100 * sc['accuracy']:4.0f}% {sc['dtpr']:.3f} {sc['geomean']:.3f}")
         out[name] = row

@@ -29,7 +29,9 @@ def predict_with_library(X, default=False):
     return np.array([fn(int(r[3]), int(r[4]), int(r[0]), int(r[1]), int(r[2])) for r in X], dtype=np.int64)
 
 
-def score(X, T, fallback=0):
+def score(X, T, fallback=None):
+    if fallback is None:
+        fallback = [int(v["fallback"]) for v in mdg.variants()]
     pred = predict_with_library(X)
     dflt = predict_with_library(X, default=True)
     y = cart.labels_from_table(T)
@@ -76,7 +78,7 @@ def main():
     Xte, Tte = tab4["X"][te], tab4["T"][te]
     ns = mdg.mdg_time_select_ns(Xte[:, 3], Xte[:, 4], Xte[:, 0], Xte[:, 1], Xte[:, 2], iters=2000)
     pred = predict_with_library(Xte)
-    t_model = cart.effective_times(Tte)[np.arange(Tte.shape[0]), pred]
+    t_model = cart.effective_times(Tte, [int(v["fallback"]) for v in mdg.variants()])[np.arange(Tte.shape[0]), pred]
     frac = ns * 1e-9 / t_model
     out["selector_overhead"] = {"ns_per_call": ns, "mean_pct_of_call": float(100 * frac.mean()),
                                 "max_pct_of_call": float(100 * frac.max())}

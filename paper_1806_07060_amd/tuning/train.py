@@ -69,6 +69,11 @@ def training_union(tab4, extra_tables, exclude_tables, seed=180607060):
     return X[perm], T[perm], [src[i] for i in perm]
 
 
+def fallback_links(variants_meta):
+    """fallback[v] for every variant, as the library reports them (mdg_variant_info)."""
+    return [int(m["fallback"]) for m in variants_meta]
+
+
 def default_dispatch(cfg1_table, variants_meta):
     """The traditional configuration (Section 5, 'default'): the tiled variant that is best on the 1024-cube
     and the direct variant that is best on the 256-cube (summed log time over the four transpose cases),
@@ -114,29 +119,31 @@ def main(argv=None):
     y = cart.labels_from_table(tab["T"])
     print(f"classes in use: {np.unique(y).size}; most frequent best variant: {tab['variants'][np.bincount(y).argmax()]}")
 
+    from .. import binding as mdg
+    meta = mdg.variants()
+    assert [m["name"] for m in meta] == tab["variants"], "timing table was written for a different variant table"
+    links = fallback_links(meta)  # what the dispatch does with an illegal prediction
+
     report = []
-    for rule in ("majority", "logratio"):
-        rows = cart.sweep(Xtr, Ttr, Xte, Tte, leaf_rule=rule)
+    for rule in ("majority", "logratio", "regret"):
+        rows = cart.sweep(Xtr, Ttr, Xte, Tte, leaf_rule=rule, fallback=links)
         print(f"\nleaf rule: {rule}\n{'model':12s} {'acc%':>6s} {'DTPR':>6s} {'geomean':>8s} {'leaves':>6s} {'height':>6s} {'classes':>7s}")
         for r in rows:
             print(f"{r['name']:12s} {100 * r['accuracy']:6.1f} {r['dtpr']:6.3f} {r['geomean']:8.3f} {r['leaves']:6d} "
                   f"{r['height']:6d} {len(r['classes']):7d}")
             report.append({k: v for k, v in r.items() if k != "tree"})
 
-    best, cv_table = cart.select_model(Xtr, Ttr, folds=args.folds)
+    best, cv_table = cart.select_model(Xtr, Ttr, fallback=links, folds=args.folds)
     print(f"\nchosen by {args.folds}-fold cross-validation on the training set: {best['name']}/{best['leaf_rule']} "
           f"(cv geomean {best['cv_geomean']:.4f})")
-    tree = cart.fit_cart(Xtr, Ttr, best["H"], best["L"], best["leaf_rule"])
+    tree = cart.fit_cart(Xtr, Ttr, best["H"], best["L"], best["leaf_rule"], links)
     pred = tree.predict(Xte)
-    held = {"accuracy": cart.accuracy(pred, cart.labels_from_table(Tte)), "dtpr": cart.dtpr(Tte, pred),
-            "geomean": cart.geomean_ratio(Tte, pred)}
+    held = {"accuracy": cart.accuracy(pred, cart.labels_from_table(Tte)), "dtpr": cart.dtpr(Tte, pred, links),
+            "geomean": cart.geomean_ratio(Tte, pred, links)}
     st = tree.stats()
     print(f"held-out: accuracy {100 * held['accuracy']:.1f}%  DTPR {held['dtpr']:.4f}  geomean {held['geomean']:.4f}  "
           f"leaves {st['leaves']} height {st['height']}")
 
-    from .. import binding as mdg
-    meta = mdg.variants()
-    assert [m["name"] for m in meta] == tab["variants"], "timing table was written for a different variant table"
     d_tiled, d_direct, d_thr = (meta[0]["id"], 0, 512.0 ** 3)
     if os.path.exists(args.cfg1):
         d_tiled, d_direct, d_thr = default_dispatch(load_table(args.cfg1), meta)

@@ -36,6 +36,27 @@ def test_variant_table_is_consistent():
         mdg.mdg_variant_info(len(vs))
 
 
+def test_fallback_chains_end_at_variant_zero_and_only_relax_the_variant():
+    vs = mdg.variants()
+    for v in vs:
+        seen, x = set(), v
+        while x["id"] != 0:
+            assert x["id"] not in seen and len(seen) < len(vs), "cycle in fallback links"
+            seen.add(x["id"])
+            nxt = vs[x["fallback"]]
+            if x["family"] == mdg.FAMILY_TILED and x["split_k"] > 1:  # fewer K slices of the same tile
+                assert nxt["family"] == x["family"] and nxt["split_k"] < x["split_k"]
+                assert (nxt["tile_m"], nxt["tile_n"], nxt["tile_k"]) == (x["tile_m"], x["tile_n"], x["tile_k"])
+            elif x["family"] == mdg.FAMILY_SKINNY:  # wider with the same split, else fewer slices, else a tile
+                assert (nxt["family"] == mdg.FAMILY_SKINNY and nxt["sub_n"] > x["sub_n"] and nxt["split_k"] == x["split_k"]) or \
+                       (nxt["family"] == mdg.FAMILY_SKINNY and nxt["sub_n"] >= x["sub_n"] and nxt["split_k"] < x["split_k"]) or \
+                       (nxt["family"] == mdg.FAMILY_TILED and nxt["split_k"] == 1)
+            else:
+                assert nxt["id"] == 0
+            x = nxt
+    assert vs[0]["fallback"] == 0
+
+
 def test_argument_validation_reports_first_bad_argument():
     ok = dict(layout=102, transA=111, transB=111, M=4, N=4, K=4, alpha=1.0, A=256, lda=4, B=256, ldb=4, beta=0.0,
               C=256, ldc=4)

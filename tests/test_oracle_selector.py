@@ -276,3 +276,18 @@ def test_expand_features_by_hand_and_saturation():
     f = so.expand_features((big, big, big, 0, 0))
     assert f[5] == big * big and f[6] == 2 ** 63 - 1  # M*N fits in 63 bits, M*N*K saturates
     assert so.expand_features((0, 9, 9, 0, 0))[5:] == (0, 0)
+
+
+def test_fallback_links_are_followed_to_the_first_legal_variant():
+    inf = math.inf
+    links = [0, 0, 1, 2]  # 3 -> 2 -> 1 -> 0
+    row = [8.0, inf, inf, inf]
+    assert so.effective_time(row, 3, links) == 8.0  # three hops
+    row = [8.0, 4.0, inf, inf]
+    assert so.effective_time(row, 3, links) == 4.0 and so.effective_time(row, 2, links) == 4.0
+    assert so.effective_time(row, 1, links) == 4.0 and so.effective_time(row, 0, links) == 8.0
+    assert so.performance_ratio([8.0, 4.0, inf, 2.0], 2, links) == 0.5
+    # a universal fallback id still works and differs where the chain stops earlier
+    assert so.effective_time(row, 3, 0) == 8.0
+    with pytest.raises(ValueError):
+        so.effective_time([inf, inf], 1, [0, 0])

@@ -78,6 +78,27 @@ def test_illegal_predictions_are_priced_as_the_fallback():
     assert cart.ratios(T, [1, 2]).tolist() == [so.performance_ratio(list(T[0]), 1), so.performance_ratio(list(T[1]), 2)]
 
 
+def test_fallback_links_price_illegal_predictions_like_the_oracle():
+    X, T, Xl, Tl = _table(220, 9, 17)
+    rng = np.random.default_rng(3)
+    T = T.copy()
+    T[rng.uniform(size=T.shape) < 0.25] = np.inf
+    T[:, 0] = np.where(np.isfinite(T[:, 0]), T[:, 0], 1.0)  # variant 0 legal everywhere
+    Tl = [list(map(float, r)) for r in T]
+    links = [0, 0, 1, 2, 3, 0, 5, 6, 7]
+    E = cart.effective_times(T, links)
+    for i in range(0, 220, 7):
+        for v in range(9):
+            assert E[i, v] == so.effective_time(Tl[i], v, links)
+    y = so.labels_from_table(Tl)
+    for rule in ("logratio", "regret"):
+        ours = cart.fit_cart(X, T, None, 3, rule, links)
+        ref = so.fit_cart(Xl, y, None, 3, rule, Tl, links)
+        assert ours.to_nested() == ref
+        pred = ours.predict(X)
+        assert cart.geomean_ratio(T, pred, links) == pytest.approx(so.geomean_ratio(Tl, pred.tolist(), links), rel=1e-12)
+
+
 def test_cross_validation_selects_a_model_without_the_heldout_set():
     X, T, _, _ = _table(250, 9, 4)
     best, table = cart.select_model(X[:200], T[:200], folds=4, H_set=(2, None), L_set=(1, 4, 0.2))
