@@ -289,6 +289,16 @@ def config_big(n_shapes=200, max_flops=2 ** 41, max_bytes=1.5e9, max_operand_byt
     return _dress(triples, 8, "big")
 
 
+def config_large_grid(values=(2048, 3072, 4096, 6144, 8192, 12288), max_flops=2.5e12, max_bytes=1.5e9,
+                      max_operand_bytes=6e8):
+    """Coarse grid over the largest sizes one GPU call is asked for here (a 'grid' dataset in the sense of
+    Section 4.1, at the top of the size range), under the same memory caps as the other sweeps."""
+    triples = [(m, n, k) for m in values for n in values for k in values
+               if 2 * m * n * k <= max_flops and 4 * (m * k + k * n + m * n) <= max_bytes
+               and 4 * max(m * k, k * n, m * n) <= max_operand_bytes]
+    return _dress(triples, 9, "large")
+
+
 # ------------------------------------------------------------------------------------------
 # synthetic timing tables for selector tests (no GPU involved)
 # ------------------------------------------------------------------------------------------
