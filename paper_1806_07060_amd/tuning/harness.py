@@ -100,12 +100,37 @@ def measure_case(case, pools, stream, variants, span_ms=1.0, spans=3, prune=6.0,
                                  pools.B.data_ptr(), pools.C.data_ptr()) != 1:
             continue
         t = time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 1, 1, 1)
+        if t > prune * best and t < 1e-3:
+            # a single cold call can be an outlier (first launch of a kernel symbol): ask once more before pruning
+            t = min(t, time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 1, 1, 1))
         if t <= prune * best:
             reps = int(min(max_reps, max(3, math.ceil(span_ms * 1e-3 / max(t, 1e-7)))))
             t = time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 1, reps, spans)
         out[v] = t
         best = min(best, t)
     return out
+
+
+def recheck_case(case, pools, stream, variants, times, span_ms=1.0, spans=3, prune=6.0, max_reps=200, below=1e-3):
+    """Second look at entries that were recorded from one probe call (slower than prune x the row's best) and are
+    short enough (< `below` seconds) for a cold first launch to have distorted them: probe again, and measure
+    fully if the new probe no longer says prune.  Returns the corrected row and the number of entries changed."""
+    c = case.resolved()
+    n_sets, sa, sb, sc = pools.layout(c)
+    out = np.array(times, dtype=np.float64)
+    best = np.min(out)
+    changed = 0
+    for v in range(len(variants)):
+        if not np.isfinite(out[v]) or out[v] <= prune * best or out[v] >= below:
+            continue
+        t = time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 2, 3, 1)
+        if t <= prune * best:
+            reps = int(min(max_reps, max(3, math.ceil(span_ms * 1e-3 / max(t, 1e-7)))))
+            t = time_variant(v, c, pools, n_sets, sa, sb, sc, stream, 1, reps, spans)
+        if t < 0.8 * out[v]:
+            out[v] = t
+            changed += 1
+    return out, changed
 
 
 def load_done(path):
@@ -156,6 +181,9 @@ def main(argv=None):
     ap.add_argument("--span-ms", type=float, default=1.0)
     ap.add_argument("--spans", type=int, default=3)
     ap.add_argument("--prune", type=float, default=6.0)
+    ap.add_argument("--recheck-from", default=None, metavar="CSV",
+                    help="a finished table of the same inputs and variants: re-measure only the short entries that "
+                         "were recorded from a single probe call, write the corrected table to --out")
     ap.add_argument("--extend-from", default=None, metavar="CSV",
                     help="a table of the same inputs written for an older variant table: times of variants it "
                          "already holds (matched by name) are copied, only the new variants are measured")
@@ -176,6 +204,29 @@ def main(argv=None):
     want_header = ["index", "name", "M", "N", "K", "tA", "tB", "alpha", "beta"] + [v["name"] for v in variants]
     if header is not None and header != want_header:
         raise SystemExit(f"{args.out} was written for a different variant table; move it away first")
+    if args.recheck_from:
+        rc_header, rc_rows = load_done(args.recheck_from)
+        if rc_header != want_header:
+            raise SystemExit(f"{args.recheck_from} was written for a different variant table")
+        t0, total = time.time(), 0
+        with open(args.out, "w", newline="") as f:
+            w = csv.writer(f)
+            w.writerow(want_header)
+            for i, c in enumerate(cases):
+                if i not in rc_rows:
+                    continue
+                r = rc_rows[i]
+                assert (int(r[2]), int(r[3]), int(r[4]), int(r[5]), int(r[6])) == (c.M, c.N, c.K, c.tA(), c.tB()), r[:7]
+                times, changed = recheck_case(c, pools, stream, variants, [float(x) for x in r[9:]], args.span_ms,
+                                              args.spans, args.prune)
+                total += changed
+                w.writerow(r[:9] + [repr(float(t)) for t in times])
+                if (i + 1) % 200 == 0:
+                    f.flush()
+                    print(f"[{time.time() - t0:7.1f}s] {i + 1}/{len(cases)} rechecked, {total} entries corrected", flush=True)
+        mdg.mdg_set_workspace(0, 0)
+        print(f"done: {total} entries corrected in {time.time() - t0:.1f}s -> {args.out}", flush=True)
+        return
     old_rows, old_names = {}, []
     if args.extend_from:
         old_header, old_rows = load_done(args.extend_from)
