@@ -1,21 +1,29 @@
 // Skinny-N kernel: products whose N is a handful of columns (fully-connected
 // layers at small batch; the "mostly rectangular" shapes Section 4.1 of the
 // paper points at).  Such calls move M*K floats of A for only 2*N flops per
-// float: they are bound by HBM bandwidth, so the kernel streams A exactly once
-// with coalesced loads and keeps NB columns of C per thread in registers.
-// No matrix cores: the arithmetic intensity is far below their ridge.
+// float: they are bound by HBM bandwidth, so the kernels stream A exactly once
+// with coalesced loads, keep NB columns of C per thread in registers and are
+// built around the number of bytes a CU has in flight (about 40 KB per CU are
+// needed to cover the memory latency at 8 TB/s).  No matrix cores: the
+// arithmetic intensity is far below their ridge.
 //
-//   A not transposed (m contiguous): one thread per row m; a wave reads 64
-//     consecutive rows per k (256 contiguous bytes), B(k, j) is wave-uniform.
-//   A transposed (k contiguous): one wave per R = 4 rows; lanes run along k,
-//     partial dot products are combined with a cross-lane butterfly.
-// K may be cut into split_k slices (more work-groups in flight for small M);
-// partial sums then go to the workspace and a reduce pass finishes C.
-// Columns beyond NB are covered by blockIdx.z.
+//   A not transposed (m contiguous): a work-group owns a strip of 64 rows; its W
+//     waves (16 for NB <= 4, else 4) each take a contiguous part of the K range,
+//     so that one row strip alone keeps 16 x 16 loads of 256 contiguous bytes in
+//     flight; lane = row, B(k, j) is wave-uniform and read with scalar loads; the
+//     W partial sums meet in LDS and are added in wave order.
+//   A transposed (k contiguous): one wave per R = 4 rows; lanes run along k with
+//     16-byte loads when the operands are aligned (two per row in flight), scalar
+//     loads otherwise; partial dot products are combined with a cross-lane butterfly.
+// K may additionally be cut into split_k slices (grid.y): partial sums then go to
+// the workspace and the reduce pass finishes C.  Columns beyond NB are covered by
+// blockIdx.z.  Every sum is formed in a fixed order: results are deterministic.
 #include "mdg_internal.h"
 #include "mdg_variant_list.h"
 
 namespace mdg {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 struct SkinnyParams {
   const float* A;
@@ -26,6 +34,7 @@ struct SkinnyParams {
   int M, N, K;
   int split_k, k_per_split;
   float alpha, beta;
+  int vec_ok;  // A-transposed path: 16-byte loads along k are aligned for A and B
 };
 
 template <bool TB>
@@ -44,45 +53,63 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams& p, int split, i
   }
 }
 
-// ---- A not transposed: thread per row ------------------------------------------------------
+// ---- A not transposed: 64-row strip per work-group, waves interleaved along k -----------------
 template <int NB, bool TB>
-__global__ __launch_bounds__(256) void skinny_n_kernel(SkinnyParams p) {
-  const int m = blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(64 * (NB <= 4 ? 16 : 4)) void skinny_n_kernel(SkinnyParams p) {
+  constexpr int W = NB <= 4 ? 16 : 4;  // waves per work-group
+  constexpr int U = 16;                // loads in flight per lane
+  __shared__ float red[W][NB][64];
+  const int lane = threadIdx.x & 63;
+  // the wave index and everything derived from it (k, the addresses of B) are wave-uniform: saying so
+  // lets B(k, j) be fetched with scalar loads instead of 64 identical vector loads
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = blockIdx.x * 64 + lane;
   const int split = blockIdx.y;
   const int n0 = blockIdx.z * NB;
   const int k_begin = split * p.k_per_split;
   const int k_end = min(p.K, k_begin + p.k_per_split);
-  const int mc = min(m, p.M - 1);
-  const float* __restrict__ a = p.A + mc;
+  const float* __restrict__ a = p.A + min(m, p.M - 1);
   float acc[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) acc[j] = 0.f;
   int jc[NB];
 #pragma unroll
-  for (int j = 0; j < NB; ++j) jc[j] = min(n0 + j, p.N - 1);
+  for (int j = 0; j < NB; ++j) jc[j] = __builtin_amdgcn_readfirstlane(min(n0 + j, p.N - 1));
 
-  int k = k_begin;
-  for (; k + 16 <= k_end; k += 16) {  // 16 independent loads in flight per lane
-    float av[16];
+  // wave w owns the contiguous k range [kw_begin, kw_end): consecutive k keep the scalar loads of B
+  // contiguous too (they merge into wide scalar loads)
+  const int kc = (max(k_end - k_begin, 0) + W - 1) / W;
+  const int kw_begin = k_begin + wave * kc, kw_end = min(k_end, kw_begin + kc);
+  int k = kw_begin;
+  for (; k + U <= kw_end; k += U) {
+    float av[U];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) av[u] = a[(int64_t)(k + u) * p.lda];
+    for (int u = 0; u < U; ++u) av[u] = a[(int64_t)(k + u) * p.lda];
 #pragma unroll
-    for (int u = 0; u < 16; ++u)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int j = 0; j < NB; ++j) acc[j] = fmaf(av[u], ld_b<TB>(p.B, p.ldb, k + u, jc[j]), acc[j]);
   }
-  for (; k < k_end; ++k) {
-    float av = a[(int64_t)k * p.lda];
+  for (; k < kw_end; ++k) {
+    const float av = a[(int64_t)k * p.lda];
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[j] = fmaf(av, ld_b<TB>(p.B, p.ldb, k, jc[j]), acc[j]);
   }
-  if (m >= p.M) return;
 #pragma unroll
-  for (int j = 0; j < NB; ++j)
-    if (n0 + j < p.N) skinny_store(p, split, m, n0 + j, acc[j]);
+  for (int j = 0; j < NB; ++j) red[wave][j][lane] = acc[j];
+  __syncthreads();
+  // NB x 64 outputs, summed over the waves in wave order by the first NB*64 threads
+  for (int o = threadIdx.x; o < NB * 64; o += 64 * W) {
+    const int j = o >> 6, l = o & 63;
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < W; ++w) s += red[w][j][l];
+    const int mm = blockIdx.x * 64 + l;
+    if (mm < p.M && n0 + j < p.N) skinny_store(p, split, mm, n0 + j, s);
+  }
 }
 
-// ---- A transposed: wave per R rows, lanes along k ------------------------------------------
+// ---- A transposed: wave per R rows, lanes along k ----------------------------------------------
 template <int NB, bool TB>
 __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
   constexpr int R = 4;
@@ -105,7 +132,46 @@ __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[r][j] = 0.f;
 
-  int k = k_begin + lane;
+  int k = k_begin;
+  if (!TB && p.vec_ok && (k_begin & 3) == 0) {
+    // 16-byte loads: a wave covers 256 consecutive k per row and trip, two trips in flight
+    for (; k + 512 <= k_end; k += 512) {
+      floatx4 a0[R], a1[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        a0[r] = *reinterpret_cast<const floatx4*>(arow[r] + k + 4 * lane);
+        a1[r] = *reinterpret_cast<const floatx4*>(arow[r] + k + 256 + 4 * lane);
+      }
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const float* bcol = p.B + (int64_t)jc[j] * p.ldb + k + 4 * lane;
+        const floatx4 b0 = *reinterpret_cast<const floatx4*>(bcol);
+        const floatx4 b1 = *reinterpret_cast<const floatx4*>(bcol + 256);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[r][j] = fmaf(a0[r][e], b0[e], acc[r][j]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[r][j] = fmaf(a1[r][e], b1[e], acc[r][j]);
+        }
+      }
+    }
+    for (; k + 256 <= k_end; k += 256) {
+      floatx4 a0[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) a0[r] = *reinterpret_cast<const floatx4*>(arow[r] + k + 4 * lane);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const floatx4 b0 = *reinterpret_cast<const floatx4*>(p.B + (int64_t)jc[j] * p.ldb + k + 4 * lane);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[r][j] = fmaf(a0[r][e], b0[e], acc[r][j]);
+      }
+    }
+  }
+  // scalar loads: unaligned operands, transposed B, and the tail of the vector path
+  k += lane;
   for (; k + 64 < k_end; k += 128) {  // two k per lane per trip
     float a0[R], a1[R], b0[NB], b1[NB];
 #pragma unroll
@@ -155,14 +221,18 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
   p.lda = g.lda, p.ldb = g.ldb, p.ldc = g.ldc;
   p.M = (int)g.M, p.N = (int)g.N, p.K = (int)g.K;
   p.split_k = split_k;
-  p.k_per_split = (int)((g.K + split_k - 1) / split_k);
+  // slices are multiples of 4 so that the 16-byte path stays aligned in every slice
+  p.k_per_split = (int)((((g.K + split_k - 1) / split_k) + 3) / 4 * 4);
   p.alpha = g.alpha, p.beta = g.beta;
+  p.vec_ok = ((g.lda & 3) == 0) && ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
+             ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
   const int64_t col_groups = (g.N + NB - 1) / NB;
   if (col_groups > 65535 || split_k > 65535) return MDG_ERR_LAUNCH;
   if (!g.tA) {
-    dim3 grid((unsigned)((g.M + 255) / 256), (unsigned)split_k, (unsigned)col_groups);
-    if (g.tB) skinny_n_kernel<NB, true><<<grid, dim3(256), 0, g.stream>>>(p);
-    else skinny_n_kernel<NB, false><<<grid, dim3(256), 0, g.stream>>>(p);
+    constexpr int W = NB <= 4 ? 16 : 4;
+    dim3 grid((unsigned)((g.M + 63) / 64), (unsigned)split_k, (unsigned)col_groups);
+    if (g.tB) skinny_n_kernel<NB, true><<<grid, dim3(64 * W), 0, g.stream>>>(p);
+    else skinny_n_kernel<NB, false><<<grid, dim3(64 * W), 0, g.stream>>>(p);
   } else {
     dim3 grid((unsigned)((g.M + 15) / 16), (unsigned)split_k, (unsigned)col_groups);
     if (g.tB) skinny_t_kernel<NB, true><<<grid, dim3(256), 0, g.stream>>>(p);

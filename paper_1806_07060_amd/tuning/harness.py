@@ -184,6 +184,9 @@ def main(argv=None):
     ap.add_argument("--recheck-from", default=None, metavar="CSV",
                     help="a finished table of the same inputs and variants: re-measure only the short entries that "
                          "were recorded from a single probe call, write the corrected table to --out")
+    ap.add_argument("--remeasure-prefix", default=None, metavar="NAME",
+                    help="with --extend-from: variants whose name starts with NAME are measured again instead of "
+                         "copied (after a change to that kernel family)")
     ap.add_argument("--extend-from", default=None, metavar="CSV",
                     help="a table of the same inputs written for an older variant table: times of variants it "
                          "already holds (matched by name) are copied, only the new variants are measured")
@@ -247,7 +250,8 @@ def main(argv=None):
             if i in old_rows:
                 r = old_rows[i]
                 assert (int(r[2]), int(r[3]), int(r[4]), int(r[5]), int(r[6])) == (c.M, c.N, c.K, c.tA(), c.tB()), r[:7]
-                known = {name_to_id[n]: float(x) for n, x in zip(old_names, r[9:]) if n in name_to_id}
+                known = {name_to_id[n]: float(x) for n, x in zip(old_names, r[9:]) if n in name_to_id
+                         and not (args.remeasure_prefix and n.startswith(args.remeasure_prefix))}
             times = measure_case(c, pools, stream, variants, args.span_ms, args.spans, args.prune, known=known)
             w.writerow([i, c.name, c.M, c.N, c.K, c.tA(), c.tB(), repr(c.alpha), repr(c.beta)] +
                        [repr(float(t)) for t in times])
