@@ -205,7 +205,7 @@ def main():
     hbm_bound = dom["flops"] / dom["bytes"] < FP32_MATRIX_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.workload == "square" and args.sizes == ap.get_default("sizes"):
         try:
             traffic = json.load(open(tpath)).get(dom_sym, {}).get("bytes_per_launch")
         except Exception:

@@ -289,6 +289,34 @@ def config_big(n_shapes=200, max_flops=2 ** 41, max_bytes=1.5e9, max_operand_byt
     return _dress(triples, 8, "big")
 
 
+def _log_uniform_sweep(config_index, prefix, n_shapes, m_range, n_range, k_range, max_flops=2 ** 38,
+                       max_operand_bytes=6e8):
+    rng = np.random.Generator(np.random.PCG64(case_seed(config_index, 0)))
+    triples = []
+
+    def draw(lo, hi):
+        return int(round(lo * (hi / lo) ** rng.uniform()))
+
+    while len(triples) < n_shapes:
+        m, n, k = draw(*m_range), draw(*n_range), draw(*k_range)
+        if 2 * m * n * k > max_flops or 4 * max(m * k, k * n, m * n) > max_operand_bytes:
+            continue
+        triples.append((m, n, k))
+    return _dress(triples, config_index, prefix)
+
+
+def config_thin(n_shapes=600):
+    """Thin products (few columns, many rows, long K): N in [1, 64], M in [256, 16384], K in [256, 8192],
+    each log-uniform.  The region of fully-connected layers at small batch."""
+    return _log_uniform_sweep(10, "thin", n_shapes, (256, 16384), (1, 64), (256, 8192))
+
+
+def config_flat(n_shapes=400):
+    """Flat products (few rows, very many columns): M in [16, 512], N in [1024, 65536], K in [16, 4096],
+    each log-uniform.  The region of convolutions lowered to GEMM."""
+    return _log_uniform_sweep(11, "flat", n_shapes, (16, 512), (1024, 65536), (16, 4096))
+
+
 def config_large_grid(values=(2048, 3072, 4096, 6144, 8192, 12288), max_flops=2.5e12, max_bytes=1.5e9,
                       max_operand_bytes=6e8):
     """Coarse grid over the largest sizes one GPU call is asked for here (a 'grid' dataset in the sense of
