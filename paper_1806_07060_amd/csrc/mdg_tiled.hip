@@ -151,11 +151,6 @@ struct OperandLoader {
 };
 
 template <int F>
-struct Frag {
-  float v[F];
-};
-
-template <int F>
 __device__ __forceinline__ void lds_read_frag(float (&dst)[F], const float* src) {
   if constexpr (F == 4) {
     floatx4 t = *reinterpret_cast<const floatx4*>(src);

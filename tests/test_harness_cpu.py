@@ -1,0 +1,84 @@
+"""The tuning harness's bookkeeping (pruning, second probe, extend and recheck modes) with a fake timer. CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_1806_07060_amd import workloads as wl
+from paper_1806_07060_amd.tuning import harness
+
+
+class FakePools:
+    class _T:
+        def data_ptr(self):
+            return 4096
+    A = B = C = _T()
+
+    def layout(self, case):
+        return 1, 64, 64, 64
+
+
+@pytest.fixture
+def fake(monkeypatch):
+    """Variants 0..3 all legal; `times[v]` is the true time, `first_call_penalty[v]` is added to the first single-call probe."""
+    state = {"times": [10e-6, 2e-6, 50e-6, 3e-6], "penalty": [0, 0, 0, 0], "calls": []}
+
+    def time_variant(v, case, pools, n_sets, sa, sb, sc, stream, warmup, reps, spans):
+        state["calls"].append((v, warmup, reps, spans))
+        t = state["times"][v]
+        if reps == 1 and state["penalty"][v]:
+            t += state["penalty"][v]
+            state["penalty"][v] = 0
+        return t
+
+    monkeypatch.setattr(harness, "time_variant", time_variant)
+    monkeypatch.setattr(harness.mdg, "mdg_variant_legal", lambda *a, **k: 1)
+    return state
+
+
+VARIANTS = [{"id": i, "family": 1 if i else 0, "name": f"v{i}"} for i in range(4)]
+CASE = wl.GemmCase(64, 64, 64)
+
+
+def test_slow_variants_are_recorded_from_probes_fast_ones_measured_fully(fake):
+    out = harness.measure_case(CASE, FakePools(), 0, VARIANTS, span_ms=1.0, spans=3, prune=6.0)
+    assert out.tolist() == fake["times"]
+    full = [c for c in fake["calls"] if c[2] > 1]
+    assert {c[0] for c in full} == {0, 1, 3}  # 50 us > 6 x 2 us: variant 2 is only probed (twice: second opinion)
+    assert [c for c in fake["calls"] if c[0] == 2] == [(2, 1, 1, 1), (2, 1, 1, 1)]
+    reps = {c[0]: c[2] for c in full}
+    assert reps[1] == min(200, math.ceil(1e-3 / 2e-6)) and reps[0] == 100
+
+
+def test_a_cold_first_probe_does_not_get_a_good_variant_pruned(fake):
+    fake["penalty"][3] = 40e-6  # first launch of this kernel symbol is slow once
+    out = harness.measure_case(CASE, FakePools(), 0, VARIANTS)
+    assert out[3] == 3e-6 and (3, 1, 1, 1) in fake["calls"] and any(c[0] == 3 and c[2] > 1 for c in fake["calls"])
+
+
+def test_known_times_are_kept_and_not_measured_again(fake):
+    out = harness.measure_case(CASE, FakePools(), 0, VARIANTS, known={1: 2.5e-6, 2: math.inf})
+    assert out[1] == 2.5e-6 and math.isinf(out[2])
+    assert {c[0] for c in fake["calls"]} == {0, 3}
+
+
+def test_recheck_only_touches_short_probe_only_entries(fake):
+    row = [10e-6, 2e-6, 50e-6, 30e-6]  # variant 3 was recorded from a cold probe; its true time is 3 us
+    out, changed = harness.recheck_case(CASE, FakePools(), 0, VARIANTS, row, prune=6.0)
+    assert changed == 1 and out.tolist() == [10e-6, 2e-6, 50e-6, 3e-6]
+    assert {c[0] for c in fake["calls"]} == {2, 3}  # entries within 6 x best are left alone
+    # long entries (>= 1 ms) are never rechecked
+    fake["calls"].clear()
+    out, changed = harness.recheck_case(CASE, FakePools(), 0, VARIANTS, [10e-6, 2e-6, 5e-3, 3e-6])
+    assert changed == 0 and fake["calls"] == []
+
+
+def test_every_configuration_index_yields_resolved_column_major_cases():
+    for cfg in range(12):
+        if cfg in (5,):
+            continue  # 3375 cases: covered by the size check below
+        cases = harness.cases_for(cfg)
+        assert cases and all(c.layout == wl.COL_MAJOR and c.lda >= 1 and c.ldb >= 1 and c.ldc >= 1 for c in cases[:50])
+    assert len(harness.cases_for(5)) == 3375
+    with pytest.raises(ValueError):
+        harness.cases_for(99)

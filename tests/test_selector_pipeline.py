@@ -200,3 +200,28 @@ def test_default_dispatch_picks_per_family_bests_on_the_two_cubes():
     T[4:] = [9.0, 9.0, 4.0, 3.0, 1.0]  # 1024-cube: best tiled without split-K is variant 3
     tiled, direct, thr = train.default_dispatch({"X": X, "T": T}, meta)
     assert (tiled, direct, thr) == (3, 1, 512.0 ** 3)
+
+
+def test_product_and_oracle_agree_on_measured_tables():
+    # the same trees on a slice of the real timing table (illegal entries, fallback links, 52 classes)
+    from paper_1806_07060_amd import binding as mdg
+    from paper_1806_07060_amd.tuning import train
+    path = os.path.join(train.RESULTS, "timings_cfg4.csv")
+    if not os.path.exists(path):
+        pytest.skip("no timing table stored")
+    tab = train.load_table(path)
+    if tab["variants"] != [v["name"] for v in mdg.variants()]:
+        pytest.skip("stored table belongs to another variant table")
+    links = train.fallback_links(mdg.variants())
+    X, T = tab["X"][:300], tab["T"][:300]
+    Xl = [so.expand_features(tuple(int(a) for a in r)) for r in X]
+    Tl = [list(map(float, r)) for r in T]
+    y = so.labels_from_table(Tl)
+    for rule, H, L in (("majority", None, 1), ("logratio", 6, 4), ("regret", 5, 3)):
+        ours = cart.fit_cart(X, T, H, L, rule, links)
+        ref = so.fit_cart(Xl, y, H, L, rule, Tl, links)
+        assert ours.to_nested() == ref, rule
+        pred = ours.predict(tab["X"][300:500])
+        assert pred.tolist() == [so.predict(ref, so.expand_features(tuple(int(a) for a in r))) for r in tab["X"][300:500]]
+        Th = [list(map(float, r)) for r in tab["T"][300:500]]
+        assert cart.dtpr(tab["T"][300:500], pred, links) == pytest.approx(so.dtpr(Th, pred.tolist(), links), rel=1e-12)
