@@ -47,7 +47,24 @@ __global__ __launch_bounds__(256) void direct_kernel(DirectParams p) {
     for (int a = 0; a < TM; ++a) mrow[a] = min(m0 + tx + 16 * a, p.M - 1);
 #pragma unroll
     for (int b = 0; b < TN; ++b) ncol[b] = min(n0 + ty + 16 * b, p.N - 1);
-    for (int k = 0; k < p.K; ++k) {
+    int k = 0;
+    for (; k + 4 <= p.K; k += 4) {  // four k per trip: their loads are independent and overlap
+      float av[4][TM], bv[4][TN];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a) av[u][a] = ld_op<TA>(p.A, p.lda, mrow[a], k + u);
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bv[u][b] = ld_op<!TB>(p.B, p.ldb, ncol[b], k + u);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) acc[a][b] = fmaf(av[u][a], bv[u][b], acc[a][b]);
+    }
+    for (; k < p.K; ++k) {
       float av[TM], bv[TN];
 #pragma unroll
       for (int a = 0; a < TM; ++a) av[a] = ld_op<TA>(p.A, p.lda, mrow[a], k);
@@ -95,6 +112,17 @@ __global__ __launch_bounds__(256) void direct_kernel(DirectParams p) {
     }
   }
 
+  // all reads of the old C first (independent loads in flight), then scale and store
+  float old[TM][TN];
+  if (p.beta != 0.f) {
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int a = 0; a < TM; ++a) {
+        const int m = min(m0 + tx + 16 * a, p.M - 1), n = min(n0 + ty + 16 * b, p.N - 1);
+        old[a][b] = p.C[(int64_t)m + (int64_t)n * p.ldc];
+      }
+  }
 #pragma unroll
   for (int b = 0; b < TN; ++b) {
     int n = n0 + ty + 16 * b;
@@ -103,10 +131,9 @@ __global__ __launch_bounds__(256) void direct_kernel(DirectParams p) {
     for (int a = 0; a < TM; ++a) {
       int m = m0 + tx + 16 * a;
       if (m >= p.M) continue;
-      float* c = p.C + (int64_t)m + (int64_t)n * p.ldc;
       float r = p.alpha * acc[a][b];
-      if (p.beta != 0.f) r = fmaf(p.beta, *c, r);
-      *c = r;
+      if (p.beta != 0.f) r = fmaf(p.beta, old[a][b], r);
+      p.C[(int64_t)m + (int64_t)n * p.ldc] = r;
     }
   }
 }
@@ -163,12 +190,19 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* ws, flo
   int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   int64_t total = (int64_t)M * N;
   if (e >= total) return;
-  float s = 0.f;
-  for (int i = 0; i < split_k; ++i) s += ws[(int64_t)i * total + e];
   int m = (int)(e % M), n = (int)(e / M);
   float* c = C + (int64_t)m + (int64_t)n * ldc;
+  const float c0 = (beta != 0.f) ? *c : 0.f;  // issued first, needed last
+  float s = 0.f;
+  for (int i0 = 0; i0 < split_k; i0 += 8) {  // eight independent loads in flight, added in slice order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (i0 + u < split_k) ? ws[(int64_t)(i0 + u) * total + e] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
   float r = alpha * s;
-  if (beta != 0.f) r = fmaf(beta, *c, r);
+  if (beta != 0.f) r = fmaf(beta, c0, r);
   *c = r;
 }
 

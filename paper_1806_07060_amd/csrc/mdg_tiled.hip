@@ -364,41 +364,56 @@ void tiled_kernel(TiledParams p) {
   const bool c_al = ((p.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
   const bool vec = (FM > 1) && c_al && (m_base + FM <= p.M);
   const float alpha = p.alpha, beta = p.beta;
+  // Per block column c: first all reads of the old C (16 independent loads in flight per lane --
+  // read-then-write one row at a time would pay the memory latency sixteen times), then scale and store.
 #pragma unroll
-  for (int c = 0; c < FN; ++c)
+  for (int c = 0; c < FN; ++c) {
+    float old[16][FM];
+    if (beta != 0.f) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
+        const float* src = p.C + (int64_t)m_base + (int64_t)min(n, p.N - 1) * p.ldc;
+        if (vec) {
+          if constexpr (FM == 4) {
+            const floatx4 v = *reinterpret_cast<const floatx4*>(src);
+            old[r][0] = v[0], old[r][1] = v[1], old[r][2] = v[2], old[r][3] = v[3];
+          } else if constexpr (FM == 2) {
+            const floatx2 v = *reinterpret_cast<const floatx2*>(src);
+            old[r][0] = v[0], old[r][1] = v[1];
+          }
+        } else {
+#pragma unroll
+          for (int b = 0; b < FM; ++b) old[r][b] = (m_base + b < p.M) ? src[b] : 0.f;
+        }
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
       if (n >= p.N) continue;
       float* dst = p.C + (int64_t)m_base + (int64_t)n * p.ldc;
+      float o[FM];
+#pragma unroll
+      for (int b = 0; b < FM; ++b) {
+        o[b] = alpha * acc[c][b][r];
+        if (beta != 0.f) o[b] = fmaf(beta, old[r][b], o[b]);
+      }
       if (vec) {
         if constexpr (FM == 4) {
-          floatx4 o = {alpha * acc[c][0][r], alpha * acc[c][1][r], alpha * acc[c][2][r], alpha * acc[c][3][r]};
-          if (beta != 0.f) {
-            floatx4 old = *reinterpret_cast<const floatx4*>(dst);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = fmaf(beta, old[e], o[e]);
-          }
-          *reinterpret_cast<floatx4*>(dst) = o;
+          const floatx4 v = {o[0], o[1], o[2], o[3]};
+          *reinterpret_cast<floatx4*>(dst) = v;
         } else if constexpr (FM == 2) {
-          floatx2 o = {alpha * acc[c][0][r], alpha * acc[c][1][r]};
-          if (beta != 0.f) {
-            floatx2 old = *reinterpret_cast<const floatx2*>(dst);
-            o[0] = fmaf(beta, old[0], o[0]);
-            o[1] = fmaf(beta, old[1], o[1]);
-          }
-          *reinterpret_cast<floatx2*>(dst) = o;
+          const floatx2 v = {o[0], o[1]};
+          *reinterpret_cast<floatx2*>(dst) = v;
         }
       } else {
 #pragma unroll
         for (int b = 0; b < FM; ++b)
-          if (m_base + b < p.M) {
-            float o = alpha * acc[c][b][r];
-            if (beta != 0.f) o = fmaf(beta, dst[b], o);
-            dst[b] = o;
-          }
+          if (m_base + b < p.M) dst[b] = o[b];
       }
     }
+  }
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN>
