@@ -305,13 +305,13 @@ def _log_uniform_sweep(config_index, prefix, n_shapes, m_range, n_range, k_range
     return _dress(triples, config_index, prefix)
 
 
-def config_thin(n_shapes=600):
+def config_thin(n_shapes=1000):
     """Thin products (few columns, many rows, long K): N in [1, 64], M in [256, 16384], K in [256, 8192],
     each log-uniform.  The region of fully-connected layers at small batch."""
     return _log_uniform_sweep(10, "thin", n_shapes, (256, 16384), (1, 64), (256, 8192))
 
 
-def config_flat(n_shapes=400):
+def config_flat(n_shapes=1200):
     """Flat products (few rows, very many columns): M in [16, 512], N in [1024, 65536], K in [16, 4096],
     each log-uniform.  The region of convolutions lowered to GEMM."""
     return _log_uniform_sweep(11, "flat", n_shapes, (16, 512), (1024, 65536), (16, 4096))
