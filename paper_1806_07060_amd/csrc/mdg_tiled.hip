@@ -7,6 +7,10 @@
 // Work decomposition (column-major C, M contiguous)
 //   work-group : BM x BN tile of C, K range [k_begin, k_end) (one slice when split_k > 1)
 //   wave       : WTM x WTN sub-tile, WTM = BM / WGM, WTN = BN / WGN, as FM x FN blocks of 32 x 32
+//   wave group : WGK groups of WGM x WGN waves share the tile; group g multiplies rows
+//                [g * BK / WGK, (g + 1) * BK / WGK) of every K step and the groups' partial
+//                sums are added through LDS at the end, in group order (a split of K inside
+//                the work-group: more waves per CU for small C without a second launch)
 //   MFMA       : v_mfma_f32_32x32x2_f32 (true fp32 operands, fp32 accumulate).
 //                The ROW operand of the instruction is fed from op(B) (index n), the
 //                COLUMN operand from op(A) (index m), i.e. each block holds a 32 x 32
@@ -170,10 +174,12 @@ constexpr int min_waves_per_simd() {
   return (BM * BN / (WGM * WGN) > 128 * 64) ? 1 : 2;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool TA, bool TB>
-__global__ __launch_bounds__(64 * WGM * WGN, (min_waves_per_simd<BM, BN, WGM, WGN>()))
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK, bool TA, bool TB>
+__global__ __launch_bounds__(64 * WGM * WGN * WGK, (min_waves_per_simd<BM, BN, WGM, WGN>()))
 void tiled_kernel(TiledParams p) {
-  constexpr int NT = 64 * WGM * WGN;
+  constexpr int NT = 64 * WGM * WGN * WGK;
+  constexpr int BKW = BK / WGK;  // rows of a K step one wave group multiplies
+  static_assert(BK % WGK == 0 && BKW % 2 == 0 && BKW >= 4, "each wave group needs whole pairs of k rows");
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int FM = WTM / 32, FN = WTN / 32;
   static_assert(FM == 1 || FM == 2 || FM == 4, "wave tile rows must be 32, 64 or 128");
@@ -185,13 +191,15 @@ void tiled_kernel(TiledParams p) {
   using LoadB = OperandLoader<BN, BK, NT, !TB>;
 
   __shared__ __attribute__((aligned(16))) float lds[2 * (A_STAGE + B_STAGE)];
+  static_assert((WGK - 1) * BM * BN <= 2 * (A_STAGE + B_STAGE), "the partial sums of the wave groups must fit the stages");
   float* As = lds;
   float* Bs = lds + 2 * A_STAGE;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int h = lane >> 5, pl = lane & 31;
-  const int wm = wave % WGM, wn = wave / WGM;
+  const int kg = wave / (WGM * WGN), wq = wave % (WGM * WGN);
+  const int wm = wq % WGM, wn = wq / WGM;
 
   // ---- which tile: undo the round-robin of work-groups over the 8 XCDs so that each
   // XCD (own L2) works on a compact block of neighbouring tiles, then walk the tiles in
@@ -255,8 +263,8 @@ void tiled_kernel(TiledParams p) {
   }
   __syncthreads();
 
-  const float* a_rd = As + h * LDA_S + wm * WTM + FM * pl;
-  const float* b_rd = Bs + h * LDB_S + wn * WTN + FN * pl;
+  const float* a_rd = As + (kg * BKW + h) * LDA_S + wm * WTM + FM * pl;
+  const float* b_rd = Bs + (kg * BKW + h) * LDB_S + wn * WTN + FN * pl;
 
   // One K step on LDS stage BUF.  Schedule (pinned with scheduling barriers):
   //   - operand registers are double-buffered: the LDS reads of sub-step kk+2 are issued before
@@ -274,15 +282,15 @@ void tiled_kernel(TiledParams p) {
     lds_read_frag<FM>(af[0], a_s);
     lds_read_frag<FN>(bf[0], b_s);
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
+    for (int kk = 0; kk < BKW; kk += 2) {
       const int cur = (kk >> 1) & 1;
-      if (kk + 2 < BK) {
+      if (kk + 2 < BKW) {
         lds_read_frag<FM>(af[cur ^ 1], a_s + (kk + 2) * LDA_S);
         lds_read_frag<FN>(bf[cur ^ 1], b_s + (kk + 2) * LDB_S);
       }
       constexpr int LS = (NS == 2) ? BUF : 0, SS = (NS == 2) ? (BUF ^ 1) : 0;  // load-target / store-source set
       if (kk == 2) load_ahead(ra[LS], rb[LS]);
-      if (kk == BK - 2 && have_next) {
+      if (kk == BKW - 2 && have_next) {
         LoadA::store(ra[SS], As + (BUF ^ 1) * A_STAGE, tid);
         LoadB::store(rb[SS], Bs + (BUF ^ 1) * B_STAGE, tid);
       }
@@ -328,6 +336,33 @@ void tiled_kernel(TiledParams p) {
     };
     if (t & 1) k_step(Buf1{}, guarded, t + 1 < n_steps);
     else k_step(Buf0{}, guarded, t + 1 < n_steps);
+  }
+
+  // ---- partial sums of wave groups 1 .. WGK-1 go through LDS (the stages are free after the last
+  // barrier of the K loop) and are added by group 0 in group order; only group 0 writes C
+  if constexpr (WGK > 1) {
+    constexpr int PER_WAVE = FN * FM * 16 * 64;
+    if (kg > 0) {
+      float* dst = lds + ((kg - 1) * (WGM * WGN) + wq) * PER_WAVE + lane;
+#pragma unroll
+      for (int c = 0; c < FN; ++c)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[((c * FM + b) * 16 + r) * 64] = acc[c][b][r];
+    }
+    __syncthreads();
+    if (kg > 0) return;
+#pragma unroll
+    for (int g2 = 1; g2 < WGK; ++g2) {
+      const float* src = lds + ((g2 - 1) * (WGM * WGN) + wq) * PER_WAVE + lane;
+#pragma unroll
+      for (int c = 0; c < FN; ++c)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[c][b][r] += src[((c * FM + b) * 16 + r) * 64];
+    }
   }
 
   // ---- epilogue
@@ -416,7 +451,7 @@ void tiled_kernel(TiledParams p) {
   }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK>
 static int launch_cfg(int split_k, const GemmArgs& g) {
   TiledParams p;
   p.A = g.A, p.B = g.B, p.C = g.C, p.ws = g.ws;
@@ -431,13 +466,13 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
   p.alpha = g.alpha, p.beta = g.beta;
   p.a_vec = ((g.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0);
   p.b_vec = ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
-  dim3 grid((unsigned)(tiles_m * tiles_n * split_k)), block(64 * WGM * WGN);
+  dim3 grid((unsigned)(tiles_m * tiles_n * split_k)), block(64 * WGM * WGN * WGK);
   if (g.tA) {
-    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, true, true><<<grid, block, 0, g.stream>>>(p);
-    else tiled_kernel<BM, BN, BK, WGM, WGN, true, false><<<grid, block, 0, g.stream>>>(p);
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, true><<<grid, block, 0, g.stream>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, false><<<grid, block, 0, g.stream>>>(p);
   } else {
-    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, false, true><<<grid, block, 0, g.stream>>>(p);
-    else tiled_kernel<BM, BN, BK, WGM, WGN, false, false><<<grid, block, 0, g.stream>>>(p);
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, true><<<grid, block, 0, g.stream>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, false><<<grid, block, 0, g.stream>>>(p);
   }
   int st = check_launch();
   if (st != MDG_OK || split_k == 1) return st;
@@ -446,9 +481,9 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
 
 int launch_tiled(int cfg, int split_k, const GemmArgs& g) {
   switch (cfg) {
-#define X(c, BM, BN, BK, WGM, WGN) \
-  case c:                          \
-    return launch_cfg<BM, BN, BK, WGM, WGN>(split_k, g);
+#define X(c, BM, BN, BK, WGM, WGN, WGK) \
+  case c:                               \
+    return launch_cfg<BM, BN, BK, WGM, WGN, WGK>(split_k, g);
     MDG_TILED_CONFIGS(X)
 #undef X
   }

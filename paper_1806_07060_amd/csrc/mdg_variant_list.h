@@ -19,22 +19,30 @@
   X(5, 4, 1, 0)               \
   X(6, 1, 4, 0)
 
-// Tiled matrix-core kernel: work-group tile BM x BN x BK, WGM x WGN waves.
-//   X(cfg, BM, BN, BK, WGM, WGN)
-#define MDG_TILED_CONFIGS(X)   \
-  X(0, 256, 256, 16, 2, 4)     \
-  X(1, 256, 128, 16, 2, 2)     \
-  X(2, 128, 256, 16, 2, 2)     \
-  X(3, 128, 128, 16, 2, 2)     \
-  X(4, 128, 128, 32, 2, 2)     \
-  X(5, 128, 64, 16, 2, 2)      \
-  X(6, 64, 128, 16, 2, 2)      \
-  X(7, 64, 64, 16, 2, 2)       \
-  X(8, 64, 64, 32, 2, 2)       \
-  X(9, 32, 32, 32, 1, 1)      \
-  X(10, 256, 256, 32, 2, 4)     \
-  X(11, 128, 32, 32, 4, 1)      \
-  X(12, 32, 128, 32, 1, 4)
+// Tiled matrix-core kernel: work-group tile BM x BN x BK, WGM x WGN waves per wave group, WGK wave
+// groups that split every K step among themselves (partial sums added through LDS).
+//   X(cfg, BM, BN, BK, WGM, WGN, WGK)
+#define MDG_TILED_CONFIGS(X)       \
+  X(0, 256, 256, 16, 2, 4, 1)      \
+  X(1, 256, 128, 16, 2, 2, 1)      \
+  X(2, 128, 256, 16, 2, 2, 1)      \
+  X(3, 128, 128, 16, 2, 2, 1)      \
+  X(4, 128, 128, 32, 2, 2, 1)      \
+  X(5, 128, 64, 16, 2, 2, 1)       \
+  X(6, 64, 128, 16, 2, 2, 1)       \
+  X(7, 64, 64, 16, 2, 2, 1)        \
+  X(8, 64, 64, 32, 2, 2, 1)        \
+  X(9, 32, 32, 32, 1, 1, 1)        \
+  X(10, 256, 256, 32, 2, 4, 1)     \
+  X(11, 128, 32, 32, 4, 1, 1)      \
+  X(12, 32, 128, 32, 1, 4, 1)      \
+  X(13, 32, 32, 64, 1, 1, 4)       \
+  X(14, 32, 32, 128, 1, 1, 8)      \
+  X(15, 64, 64, 64, 2, 2, 4)       \
+  X(16, 64, 64, 32, 2, 2, 2)       \
+  X(17, 128, 128, 32, 2, 2, 2)     \
+  X(18, 64, 32, 32, 2, 1, 1)       \
+  X(19, 32, 64, 32, 1, 2, 1)
 
 // Skinny-N kernel: streams A once; NB columns of C are held per thread.
 //   X(cfg, NB)
@@ -99,4 +107,13 @@
   V(SKINNY, 3, 8)       \
   V(SKINNY, 0, 32)      \
   V(SKINNY, 1, 32)      \
-  V(SKINNY, 2, 32)
+  V(SKINNY, 2, 32)      \
+  V(TILED, 13, 1)       \
+  V(TILED, 14, 1)       \
+  V(TILED, 15, 1)       \
+  V(TILED, 16, 1)       \
+  V(TILED, 17, 1)       \
+  V(TILED, 13, 4)       \
+  V(TILED, 15, 4)       \
+  V(TILED, 18, 1)       \
+  V(TILED, 19, 1)

@@ -94,7 +94,8 @@ def _variant_named(prefix):
 
 
 @pytest.mark.parametrize("prefix", ["direct_64x64", "direct_16x16", "tiled_128x128x16_w2x2_sk1", "tiled_32x32x32_w1x1_sk1",
-                                    "tiled_32x32x32_w1x1_sk4", "skinny_nb4_sk1"])
+                                    "tiled_32x32x32_w1x1_sk4", "tiled_32x32x64_w1x1x4_sk1", "tiled_64x64x32_w2x2x2_sk1",
+                                    "skinny_nb4_sk1"])
 def test_brute_force_tiny_shapes(prefix):
     # every combination of tiny sizes, all transposes, tight and padded leading dimensions
     gu = _gu()

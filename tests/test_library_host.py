@@ -28,10 +28,16 @@ def test_variant_table_is_consistent():
     assert fams == {mdg.FAMILY_DIRECT, mdg.FAMILY_TILED, mdg.FAMILY_SKINNY}
     for v in vs:
         assert v["id"] == vs.index(v)
-        assert v["threads"] in (64, 128, 256, 512) and v["split_k"] >= 1
+        assert v["threads"] in (64, 128, 256, 512, 1024) and v["split_k"] >= 1
         if v["family"] == mdg.FAMILY_TILED:
             assert v["tile_m"] % v["sub_m"] == 0 and v["sub_m"] in (32, 64, 128)
-            assert (v["tile_m"] // v["sub_m"]) * (v["tile_n"] // v["sub_n"]) * 64 == v["threads"]
+            # threads = 64 x waves over the tile x wave groups that split each K step
+            waves = (v["tile_m"] // v["sub_m"]) * (v["tile_n"] // v["sub_n"])
+            assert v["threads"] % (64 * waves) == 0
+            wgk = v["threads"] // (64 * waves)
+            assert v["tile_k"] % wgk == 0 and (v["tile_k"] // wgk) % 2 == 0
+            if wgk > 1:
+                assert f"x{wgk}_sk{v['split_k']}" in v["name"]
     with pytest.raises(ValueError):
         mdg.mdg_variant_info(len(vs))
 
