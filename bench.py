@@ -49,6 +49,8 @@ def kernel_symbol(desc, tA, tB):
         return f"tiled_kernel<{desc['tile_m']}, {desc['tile_n']}, {desc['tile_k']}, {wgm}, {wgn}, {wgk}, {b(tA)}, {b(tB)}>"
     if desc["family"] == 0:
         return f"direct_kernel<{desc['sub_m']}, {desc['sub_n']}, {b(desc['lds'])}, {b(tA)}, {b(tB)}>"
+    if desc["name"].startswith("skinny_mfma"):  # last argument: 16-byte loads, the case for aligned operands
+        return f"thin_mfma_kernel<{b(tA)}, {b(tB)}, {desc['sub_n'] // 16}, true>"
     return f"skinny_{'t' if tA else 'n'}_kernel<{desc['sub_n']}, {b(tB)}>"
 
 

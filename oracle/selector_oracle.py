@@ -9,8 +9,9 @@ Section 4.2; metrics of Section 5.2), step by step and in the paper's notation:
   a-bar(s)         argmax_a f_a(s): the best variant of each input (the label)
   X, Y             first 80 % / last 20 % of the (already shuffled) inputs
   CART             binary decision tree on integer features of I = (M, N, K, tA, tB):
-                   the raw values plus M*N and M*N*K (expand_features; the paper uses
-                   the raw triple only -- the products are this build's addition)
+                   the raw values plus M*N, M*N*K and the padding a grid of 32-, 64- or
+                   128-wide tiles adds to M and to N (expand_features; the paper uses
+                   the raw triple only -- the derived values are this build's addition)
                    grown with the Gini impurity, limited by H (maximum height,
                    None = unlimited) and L (minimum samples per leaf: an integer,
                    or a fraction in (0, 1) of the training samples)
@@ -51,15 +52,21 @@ most frequent label, and scikit-learn's CART where no ties occur.
 from fractions import Fraction
 import math
 
-FEATURE_NAMES = ("M", "N", "K", "tA", "tB", "MN", "MNK")
+FEATURE_NAMES = ("M", "N", "K", "tA", "tB", "MN", "MNK", "padM32", "padM64", "padM128", "padN32", "padN64", "padN128")
 INT64_MAX = 2 ** 63 - 1
 
 
 def expand_features(x):
-    """Input description (M, N, K, tA, tB) -> the seven tree features: the five raw values, the size of C
-    (M*N) and the work (M*N*K), the products saturating at 2^63 - 1 like the 64-bit code that evaluates the tree."""
+    """Input description (M, N, K, tA, tB) -> the thirteen tree features: the five raw values, the size of C
+    (M*N) and the work (M*N*K), the products saturating at 2^63 - 1 like the 64-bit code that evaluates the tree,
+    and how many rows (columns) a grid of 32-, 64-, 128-wide tiles adds beyond M (N): 0 for an exact multiple."""
     M, N, K, tA, tB = x
-    return (M, N, K, tA, tB, min(M * N, INT64_MAX), min(M * N * K, INT64_MAX))
+    pad = []
+    for size in (M, N):
+        for width in (32, 64, 128):
+            tiles = -(-size // width)  # ceiling
+            pad.append(tiles * width - size)
+    return (M, N, K, tA, tB, min(M * N, INT64_MAX), min(M * N * K, INT64_MAX)) + tuple(pad)
 
 
 # ----- labelling ---------------------------------------------------------------------------

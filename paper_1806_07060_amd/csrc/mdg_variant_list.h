@@ -44,13 +44,16 @@
   X(18, 64, 32, 32, 2, 1, 1)       \
   X(19, 32, 64, 32, 1, 2, 1)
 
-// Skinny-N kernel: streams A once; NB columns of C are held per thread.
-//   X(cfg, NB)
+// Skinny-N kernels: stream A once; NB columns of C per pass over A.
+//   X(cfg, NB, MATRIX)   MATRIX = 0: vector-ALU kernels, NB columns held per thread
+//                        MATRIX = 1: 16x16x4 matrix-core kernel, NB = 16 or 32 columns per wave
 #define MDG_SKINNY_CONFIGS(X) \
-  X(0, 1)                     \
-  X(1, 4)                     \
-  X(2, 8)                     \
-  X(3, 16)
+  X(0, 1, 0)                  \
+  X(1, 4, 0)                  \
+  X(2, 8, 0)                  \
+  X(3, 16, 0)                 \
+  X(4, 16, 1)                 \
+  X(5, 32, 1)
 
 // The variants: (family, cfg, split_k).  Order defines the public variant ids;
 // id 0 must be legal for every input (the universal fallback).
@@ -116,4 +119,8 @@
   V(TILED, 13, 4)       \
   V(TILED, 15, 4)       \
   V(TILED, 18, 1)       \
-  V(TILED, 19, 1)
+  V(TILED, 19, 1)       \
+  V(SKINNY, 4, 1)       \
+  V(SKINNY, 5, 1)       \
+  V(SKINNY, 4, 4)       \
+  V(SKINNY, 5, 4)

@@ -6,8 +6,10 @@ Section 5.2 (accuracy and DTPR) of the paper:
 
   label(s)   = argmax_a f_a(s) = the variant with the smallest measured time
   tree       = CART on integer features of the input description (M, N, K, tA, tB):
-               the five raw values plus the two products M*N (size of C, i.e. how many
-               tiles there are to share among the CUs) and M*N*K (the work), Gini impurity
+               the five raw values, the two products M*N (size of C, i.e. how many
+               tiles there are to share among the CUs) and M*N*K (the work), and six
+               tile-fit values: the rows (columns) a 32-, 64- or 128-wide tile grid adds
+               beyond M (N), 0 when the size is an exact multiple; Gini impurity
   DTPR       = mean over inputs of f_predicted / f_best
 
 Rules fixed where the paper leaves them open: fractional L = ceil(L * n)
@@ -38,13 +40,16 @@ import math
 import numpy as np
 
 RAW_FEATURES = ("M", "N", "K", "tA", "tB")
-FEATURES = RAW_FEATURES + ("MN", "MNK")
+TILE_WIDTHS = (32, 64, 128)
+FEATURES = (RAW_FEATURES + ("MN", "MNK") + tuple(f"padM{t}" for t in TILE_WIDTHS)
+            + tuple(f"padN{t}" for t in TILE_WIDTHS))
 INT64_MAX = (1 << 63) - 1
 
 
 def expand_features(X):
-    """[n, 5] raw (M, N, K, tA, tB) -> [n, 7] with M*N and M*N*K appended (saturating at INT64_MAX,
-    exactly as the generated C++ computes them).  Arrays that already have 7 columns pass through."""
+    """[n, 5] raw (M, N, K, tA, tB) -> [n, 13]: M*N and M*N*K appended (saturating at INT64_MAX, exactly as
+    the generated C++ computes them), then padM32, padM64, padM128, padN32, padN64, padN128 with
+    pad<X><t> = (t - X mod t) mod t.  Arrays that already have 13 columns pass through."""
     X = np.asarray(X, dtype=np.int64).reshape(-1, np.asarray(X).shape[-1])
     if X.shape[1] == len(FEATURES):
         return X
@@ -52,7 +57,8 @@ def expand_features(X):
     mn = [int(m) * int(n) for m, n in zip(X[:, 0].tolist(), X[:, 1].tolist())]  # Python ints: no overflow
     mnk = [min(a * int(k), INT64_MAX) for a, k in zip(mn, X[:, 2].tolist())]
     mn = [min(a, INT64_MAX) for a in mn]
-    return np.column_stack([X, np.array(mn, dtype=np.int64), np.array(mnk, dtype=np.int64)])
+    pads = [(t - X[:, c] % t) % t for c in (0, 1) for t in TILE_WIDTHS]
+    return np.column_stack([X, np.array(mn, dtype=np.int64), np.array(mnk, dtype=np.int64)] + pads)
 H_SET = (1, 2, 4, 8, None)
 L_SET = (1, 2, 4, 0.1, 0.2, 0.3, 0.4, 0.5)
 
@@ -218,7 +224,7 @@ def _best_split_regret(X, cost, idx, L_abs):
 
 
 def fit_cart(X, times, H=None, L=1, leaf_rule="majority", fallback=0, labels=None):
-    """Grow a tree on the inputs X [n, 5] (expanded to the 7 features) and the timing table `times` [n, V]."""
+    """Grow a tree on the inputs X [n, 5] (expanded to the 13 features) and the timing table `times` [n, V]."""
     X = expand_features(X)
     T = np.asarray(times, dtype=np.float64)
     y = labels_from_table(T) if labels is None else np.asarray(labels, dtype=np.int64)

@@ -171,13 +171,17 @@ def cases_for(config):
         return [c.resolved() for c in wl.config_thin()]
     if config == 11:
         return [c.resolved() for c in wl.config_flat()]
+    if config == 12:
+        return [c.resolved() for c in wl.config_thin_grid()]
+    if config == 13:
+        return [c.resolved() for c in wl.config_flat_grid()]
     raise ValueError(config)
 
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, default=4,
-                    help="0-4: the five workload configurations; 5: go2 grid; 6: po2 grid; 7: wide random sweep; 8: large products; 9: coarse grid of the largest sizes; 10: thin (few columns); 11: flat (few rows)")
+                    help="0-4: the five workload configurations; 5: go2 grid; 6: po2 grid; 7: wide random sweep; 8: large products; 9: coarse grid of the largest sizes; 10: thin (few columns); 11: flat (few rows); 12 / 13: geometric grids over the thin / flat corners")
     ap.add_argument("--out", required=True)
     ap.add_argument("--start", type=int, default=0)
     ap.add_argument("--limit", type=int, default=10 ** 9)

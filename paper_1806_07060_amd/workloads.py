@@ -317,6 +317,37 @@ def config_flat(n_shapes=1200):
     return _log_uniform_sweep(11, "flat", n_shapes, (16, 512), (1024, 65536), (16, 4096))
 
 
+def _geometric_grid(lo, hi):
+    """Powers of two from lo to hi and the values half-way between them (3 * 2^e), ascending."""
+    vals, v = [], lo
+    while v <= hi:
+        vals.append(v)
+        if v >= 2 and v + v // 2 <= hi:
+            vals.append(v + v // 2)
+        v *= 2
+    return vals
+
+
+def config_thin_grid(max_flops=2 ** 38, max_operand_bytes=6e8):
+    """Sparse geometric grid over the thin corner (a 'power of two' dataset in the sense of Section 4.1, moved to
+    where fully-connected layers at small batch live): N a power of two up to 128, M and K powers of two and
+    their midpoints.  Random sweeps almost never draw an N that is exactly 16 or 32, which is where the
+    32-column tiles fit without waste; a grid does."""
+    ns = [1, 2, 4, 8, 16, 32, 64, 128]
+    triples = [(m, n, k) for m in _geometric_grid(256, 16384) for n in ns for k in _geometric_grid(256, 8192)
+               if 2 * m * n * k <= max_flops and 4 * max(m * k, k * n, m * n) <= max_operand_bytes]
+    return _dress(triples, 12, "tgrid")
+
+
+def config_flat_grid(max_flops=2 ** 38, max_operand_bytes=6e8):
+    """Sparse geometric grid over the flat corner (few rows, very many columns: convolutions lowered to GEMM):
+    M a power of two from 16 to 512, N and K powers of two and their midpoints."""
+    ms = [16, 32, 64, 128, 256, 512]
+    triples = [(m, n, k) for m in ms for n in _geometric_grid(1024, 65536) for k in _geometric_grid(16, 4096)
+               if 2 * m * n * k <= max_flops and 4 * max(m * k, k * n, m * n) <= max_operand_bytes]
+    return _dress(triples, 13, "fgrid")
+
+
 def config_large_grid(values=(2048, 3072, 4096, 6144, 8192, 12288), max_flops=2.5e12, max_bytes=1.5e9,
                       max_operand_bytes=6e8):
     """Coarse grid over the largest sizes one GPU call is asked for here (a 'grid' dataset in the sense of

@@ -117,6 +117,33 @@ def test_brute_force_tiny_shapes(prefix):
         gu.check_against_oracle(case, got, A, B, C0, exact=True)
 
 
+@pytest.mark.parametrize("M,N,K", [(260, 16, 4096), (1027, 21, 2304), (64, 64, 4100), (512, 5, 8192), (4, 128, 300)])
+def test_thin_matrix_core_variants_long_k(M, N, K):
+    # K long enough for every wave to run its unguarded main loop (eight 16-byte loads in flight), rows and
+    # columns that are / are not multiples of the 16-wide blocks, aligned (16-byte loads) and padded operands;
+    # integer data, so every summation order must give the oracle's bits
+    gu = _gu()
+    thin = [d["id"] for d in mdg.variants() if d["name"].startswith("skinny_mfma")]
+    assert len(thin) >= 2
+    for i, (tA, tB) in enumerate(TT):
+        for pad in ((0, 0, 0), (4, 8, 4), (1, 3, 2)):
+            base = GemmCase(M, N, K, tA, tB, 1.5, (0.0, -0.5)[i % 2], dist="smallint", c0="smallint",
+                            seed=wl.case_seed(15, 100 * i + M + N), name=f"thin/{M}x{N}x{K}/{tA}{tB}/{pad}").resolved()
+            case = GemmCase(**{**base.__dict__, "lda": base.lda + pad[0], "ldb": base.ldb + pad[1], "ldc": base.ldc + pad[2]})
+            A, B, C0 = wl.make_operands(case)
+            ref = gu.oracle_result(case, A, B, C0)
+            legal = gu.legal_variants(case)
+            for v in thin:
+                if v not in legal:
+                    continue
+                st, got, *_ = gu.run_case(case, variant=v)
+                assert st == 0, (v, mdg.mdg_status_string(st))
+                try:
+                    gu.check_against_oracle(case, got, A, B, C0, exact=True, ref=ref)
+                except AssertionError as e:
+                    raise AssertionError(f"variant {mdg.mdg_variant_info(v)['name']}: {e}") from None
+
+
 @pytest.mark.parametrize("layout", [CM, RM])
 def test_special_scalars_degenerate_sizes_and_layouts(layout):
     gu = _gu()

@@ -270,12 +270,19 @@ def test_regret_trees_never_score_below_their_own_root_and_respect_limits():
 
 
 def test_expand_features_by_hand_and_saturation():
-    assert so.expand_features((3, 5, 7, 1, 0)) == (3, 5, 7, 1, 0, 15, 105)
-    assert so.expand_features((8192, 8192, 8192, 0, 1)) == (8192, 8192, 8192, 0, 1, 2 ** 26, 2 ** 39)
+    # padding by hand: 3 rows -> 29 / 61 / 125 more to the next multiple of 32 / 64 / 128; 5 columns -> 27 / 59 / 123
+    assert so.expand_features((3, 5, 7, 1, 0)) == (3, 5, 7, 1, 0, 15, 105, 29, 61, 125, 27, 59, 123)
+    # exact multiples add nothing
+    assert so.expand_features((8192, 8192, 8192, 0, 1)) == (8192, 8192, 8192, 0, 1, 2 ** 26, 2 ** 39) + (0,) * 6
+    # 96 = 3 x 32 fits the 32-grid, needs 32 more for the 64- and the 128-grid; 100 -> 28, 28, 28
+    assert so.expand_features((96, 100, 1, 0, 0))[7:] == (0, 32, 32, 28, 28, 28)
+    assert so.expand_features((129, 127, 1, 0, 0))[7:] == (31, 63, 127, 1, 1, 1)
     big = 2 ** 31 - 1
     f = so.expand_features((big, big, big, 0, 0))
     assert f[5] == big * big and f[6] == 2 ** 63 - 1  # M*N fits in 63 bits, M*N*K saturates
-    assert so.expand_features((0, 9, 9, 0, 0))[5:] == (0, 0)
+    assert f[7:] == (1, 1, 1, 1, 1, 1)  # 2^31 - 1 is one short of a multiple of every power of two
+    assert so.expand_features((0, 9, 9, 0, 0))[5:7] == (0, 0)
+    assert so.expand_features((0, 9, 9, 0, 0))[7:10] == (0, 0, 0)
 
 
 def test_fallback_links_are_followed_to_the_first_legal_variant():
