@@ -114,6 +114,13 @@ int mdg_sgemm_variant(int variant, int layout, int transA, int transB, int64_t M
  */
 int mdg_select(int transA, int transB, int64_t M, int64_t N, int64_t K);
 
+/*
+ * What mdg_sgemm itself asks: the same model behind a memo of the shapes this thread asked about recently
+ * (1024 entries in 512 two-way sets, thread-local).  Returns exactly what mdg_select returns; a repeated shape costs a
+ * few nanoseconds instead of a model evaluation (Section 5.3 discusses the overhead of the model at run time).
+ */
+int mdg_select_memo(int transA, int transB, int64_t M, int64_t N, int64_t K);
+
 /* The traditional dispatch the paper compares against (Section 5, "default"): one tiled and one direct
    configuration switched by a size threshold. */
 int mdg_select_default(int transA, int transB, int64_t M, int64_t N, int64_t K);
@@ -175,6 +182,10 @@ int mdg_time_calls(int variant, int transA, int transB, int64_t M, int64_t N, in
  */
 double mdg_time_select_ns(const int32_t* transA, const int32_t* transB, const int64_t* M, const int64_t* N,
                           const int64_t* K, int64_t n, int iters);
+
+/* The same measurement through mdg_select_memo: what a caller pays when its shapes repeat. */
+double mdg_time_select_memo_ns(const int32_t* transA, const int32_t* transB, const int64_t* M, const int64_t* N,
+                               const int64_t* K, int64_t n, int iters);
 
 #ifdef __cplusplus
 }

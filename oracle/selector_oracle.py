@@ -15,6 +15,9 @@ Section 4.2; metrics of Section 5.2), step by step and in the paper's notation:
                    grown with the Gini impurity, limited by H (maximum height,
                    None = unlimited) and L (minimum samples per leaf: an integer,
                    or a fraction in (0, 1) of the training samples)
+  forest           several such trees, each grown on a bootstrap sample whose row indices are an
+                   input; leaves list the mean integer cost of their cheapest variants and the
+                   forest predicts the variant with the smallest summed cost (see 'forest' below)
   accuracy         right predictions / test instances
   DTPR             mean over the test inputs of f_pred(s) / f_best(s)
 
@@ -225,6 +228,69 @@ def predict(tree, x):
     while "leaf" not in node:
         node = node["left"] if x[node["feature"]] <= node["threshold"] else node["right"]
     return node["leaf"]
+
+
+# ----- forest ------------------------------------------------------------------------------
+# Bagging (one of the "more effective models" the paper's conclusion leaves to future work): tree t is grown on
+# the rows bootstrap[t] of the training set (indices drawn with replacement by the caller -- this module draws
+# no random numbers).  Leaves do not vote for a class; each carries the mean cost of its cheapest variants.
+
+FOREST_KEEP = 8
+COST_CAP = 2 ** 26
+
+
+def _leaf_of(tree, x):
+    node = tree
+    while "leaf" not in node:
+        node = node["left"] if x[node["feature"]] <= node["threshold"] else node["right"]
+    return node
+
+
+def attach_leaf_costs(tree, X, cost_rows):
+    """For every leaf: mean cost (floor of sum / count, each cost capped at COST_CAP) of every variant over the
+    rows that end in the leaf; the FOREST_KEEP variants with the lowest (mean, id) are listed with their means
+    ('ids', 'costs'), and 'rest' is the mean of the next one in that order (of the last one if none is left)."""
+    sums = {}
+    for x, c in zip(X, cost_rows):
+        leaf = _leaf_of(tree, x)
+        acc = sums.setdefault(id(leaf), (leaf, [0] * len(c), [0]))
+        for v, cv in enumerate(c):
+            acc[1][v] += min(cv, COST_CAP)
+        acc[2][0] += 1
+    for leaf, total, count in sums.values():
+        mean = [t // count[0] for t in total]
+        order = sorted(range(len(mean)), key=lambda v: (mean[v], v))
+        kept = order[:FOREST_KEEP]
+        leaf["ids"] = kept
+        leaf["costs"] = [mean[v] for v in kept]
+        leaf["rest"] = mean[order[FOREST_KEEP]] if len(order) > FOREST_KEEP else mean[order[-1]]
+    return tree
+
+
+def fit_forest(X, y, table, bootstrap, H=None, L=4, leaf_rule="logratio", fallback=0):
+    cost = regret_cost_rows(table, fallback)
+    trees = []
+    for idx in bootstrap:
+        Xb, yb, Tb = [X[i] for i in idx], [y[i] for i in idx], [table[i] for i in idx]
+        tree = fit_cart(Xb, yb, H, L, leaf_rule, Tb, fallback)
+        trees.append(attach_leaf_costs(tree, Xb, [cost[i] for i in idx]))
+    return trees
+
+
+def forest_scores(trees, x, n_variants):
+    """Summed cost of every variant: a tree contributes the listed mean cost of its leaf, or the leaf's 'rest'."""
+    total = [0] * n_variants
+    for tree in trees:
+        leaf = _leaf_of(tree, x)
+        listed = dict(zip(leaf["ids"], leaf["costs"]))
+        for v in range(n_variants):
+            total[v] += listed.get(v, leaf["rest"])
+    return total
+
+
+def predict_forest(trees, x, n_variants):
+    total = forest_scores(trees, x, n_variants)
+    return total.index(min(total))  # first minimum = lowest id
 
 
 def tree_stats(tree):

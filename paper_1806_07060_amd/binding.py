@@ -24,7 +24,7 @@ FAMILY_NAMES = {0: "direct", 1: "tiled", 2: "skinny"}
 # every symbol include/mdg_sgemm.h declares
 EXPORTS = ("mdg_sgemm", "mdg_sgemm_variant", "mdg_select", "mdg_select_default", "mdg_selector_name",
            "mdg_variant_count", "mdg_variant_info", "mdg_variant_legal", "mdg_workspace_bytes", "mdg_set_workspace",
-           "mdg_status_string", "mdg_time_calls", "mdg_time_select_ns")
+           "mdg_status_string", "mdg_time_calls", "mdg_time_select_ns", "mdg_select_memo", "mdg_time_select_memo_ns")
 
 
 class VariantDesc(ctypes.Structure):
@@ -55,6 +55,7 @@ def lib():
     L.mdg_sgemm_variant.argtypes, L.mdg_sgemm_variant.restype = [ci] + gemm, ci
     L.mdg_select.argtypes, L.mdg_select.restype = [ci, ci, i64, i64, i64], ci
     L.mdg_select_default.argtypes, L.mdg_select_default.restype = [ci, ci, i64, i64, i64], ci
+    L.mdg_select_memo.argtypes, L.mdg_select_memo.restype = [ci, ci, i64, i64, i64], ci
     L.mdg_selector_name.argtypes, L.mdg_selector_name.restype = [], ctypes.c_char_p
     L.mdg_variant_count.argtypes, L.mdg_variant_count.restype = [], ci
     L.mdg_variant_info.argtypes, L.mdg_variant_info.restype = [ci, ctypes.POINTER(VariantDesc)], ci
@@ -68,6 +69,8 @@ def lib():
     L.mdg_time_calls.restype = ci
     p32, p64 = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
     L.mdg_time_select_ns.argtypes, L.mdg_time_select_ns.restype = [p32, p32, p64, p64, p64, i64, ci], ctypes.c_double
+    L.mdg_time_select_memo_ns.argtypes = [p32, p32, p64, p64, p64, i64, ci]
+    L.mdg_time_select_memo_ns.restype = ctypes.c_double
     _lib = L
     return L
 
@@ -83,6 +86,10 @@ def mdg_sgemm_variant(variant, layout, transA, transB, M, N, K, alpha, A, lda, B
 
 def mdg_select(transA, transB, M, N, K):
     return int(lib().mdg_select(transA, transB, M, N, K))
+
+
+def mdg_select_memo(transA, transB, M, N, K):
+    return int(lib().mdg_select_memo(transA, transB, M, N, K))
 
 
 def mdg_select_default(transA, transB, M, N, K):
@@ -130,11 +137,12 @@ def mdg_time_calls(variant, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta
     return int(st), [float(x) for x in out]
 
 
-def mdg_time_select_ns(transA, transB, M, N, K, iters=100):
+def mdg_time_select_ns(transA, transB, M, N, K, iters=100, memo=False):
     n = len(M)
     a32 = lambda v: (ctypes.c_int32 * n)(*[int(x) for x in v])
     a64 = lambda v: (ctypes.c_int64 * n)(*[int(x) for x in v])
-    return float(lib().mdg_time_select_ns(a32(transA), a32(transB), a64(M), a64(N), a64(K), n, iters))
+    fn = lib().mdg_time_select_memo_ns if memo else lib().mdg_time_select_ns
+    return float(fn(a32(transA), a32(transB), a64(M), a64(N), a64(K), n, iters))
 
 
 def variants():

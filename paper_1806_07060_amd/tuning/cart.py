@@ -33,6 +33,17 @@ node's cost is the smallest column sum over its inputs (the loss of the best
 single variant for that node), and a split is chosen to minimise the summed
 cost of its two children.  Integer costs keep every comparison exact.  A node
 whose cost is zero is not split; its label is the minimising variant.
+
+Forest (another of those "more effective models"): several trees, each grown on
+a bootstrap sample of the training inputs (the sample indices are an input of
+fit_forest, drawn by the seeded generator in workloads.py).  A leaf does not
+vote for one variant; it carries, for the FOREST_KEEP variants that are cheapest
+on the bootstrap inputs it holds, their mean integer cost floor(sum / count)
+(costs as in 'regret', capped at COST_CAP), and `rest`, the mean cost of the
+next cheapest variant, which stands in for every variant not listed.  The
+forest predicts the variant with the smallest cost summed over its trees (ties
+to the lowest id).  Everything is integer arithmetic, so the numpy code here,
+the plain-Python oracle and the generated C++ agree bit for bit.
 """
 from fractions import Fraction
 import math
@@ -136,10 +147,11 @@ class Tree:
         self.n.append(n)
         return len(self.n) - 1
 
-    def predict(self, X):
+    def apply(self, X):
+        """Index of the leaf node every input ends in."""
         X = expand_features(X)
         feature, threshold = np.array(self.feature), np.array(self.threshold)
-        left, right, label = np.array(self.left), np.array(self.right), np.array(self.label)
+        left, right = np.array(self.left), np.array(self.right)
         node = np.zeros(X.shape[0], dtype=np.int64)
         active = feature[node] >= 0
         while active.any():
@@ -147,7 +159,10 @@ class Tree:
             go_left = X[active, f] <= threshold[node[active]]
             node[active] = np.where(go_left, left[node[active]], right[node[active]])
             active = feature[node] >= 0
-        return label[node]
+        return node
+
+    def predict(self, X):
+        return np.array(self.label)[self.apply(X)]
 
     def stats(self):
         leaves = [i for i, f in enumerate(self.feature) if f < 0]
@@ -158,11 +173,15 @@ class Tree:
         return {"leaves": len(leaves), "height": depth(0), "classes": sorted({self.label[i] for i in leaves}),
                 "min_leaf_samples": min(self.n[i] for i in leaves)}
 
-    def to_nested(self):
-        """Nested-dict form (same shape as the oracle's trees; used by tests and the code generator)."""
+    def to_nested(self, payload=None):
+        """Nested-dict form (same shape as the oracle's trees; used by tests and the code generator).
+        `payload` maps leaf node index -> extra keys of that leaf (the cost lists of a forest member)."""
         def rec(i):
             if self.feature[i] < 0:
-                return {"leaf": int(self.label[i]), "n": int(self.n[i])}
+                leaf = {"leaf": int(self.label[i]), "n": int(self.n[i])}
+                if payload is not None:
+                    leaf.update(payload[i])
+                return leaf
             return {"feature": int(self.feature[i]), "threshold": int(self.threshold[i]), "n": int(self.n[i]),
                     "left": rec(self.left[i]), "right": rec(self.right[i])}
         return rec(0)
@@ -310,3 +329,97 @@ def select_model(X_train, T_train, fallback=0, folds=5, H_set=H_SET, L_set=L_SET
                               "cv_geomean": cross_validate(X_train, T_train, H, L, rule, fallback, folds)})
     best = max(table, key=lambda r: r["cv_geomean"])  # first maximum in sweep order
     return best, table
+
+
+FOREST_KEEP = 8
+COST_CAP = 1 << 26
+
+
+class Forest:
+    """Trees plus, per tree, the leaf cost lists: ids[node, FOREST_KEEP] (-1 = unused), costs[node, FOREST_KEEP],
+    rest[node]."""
+
+    def __init__(self, trees, ids, costs, rest, n_variants):
+        self.trees, self.ids, self.costs, self.rest, self.n_variants = trees, ids, costs, rest, n_variants
+
+    def scores(self, X):
+        X = expand_features(X)
+        total = np.zeros((X.shape[0], self.n_variants), dtype=np.int64)
+        rows = np.arange(X.shape[0])
+        for tree, ids, costs, rest in zip(self.trees, self.ids, self.costs, self.rest):
+            leaf = tree.apply(X)
+            total += rest[leaf][:, None]
+            for e in range(ids.shape[1]):
+                v = ids[leaf, e]
+                ok = v >= 0
+                np.add.at(total, (rows[ok], v[ok]), costs[leaf, e][ok] - rest[leaf][ok])
+        return total
+
+    def predict(self, X):
+        return np.argmin(self.scores(X), axis=1).astype(np.int64)  # first minimum = lowest id
+
+    def stats(self):
+        st = [t.stats() for t in self.trees]
+        return {"trees": len(self.trees), "leaves": int(sum(s["leaves"] for s in st)),
+                "height": int(max(s["height"] for s in st))}
+
+    def to_nested(self):
+        out = []
+        for tree, ids, costs, rest in zip(self.trees, self.ids, self.costs, self.rest):
+            payload = {}
+            for i, f in enumerate(tree.feature):
+                if f < 0:
+                    keep = ids[i] >= 0
+                    payload[i] = {"ids": [int(v) for v in ids[i][keep]], "costs": [int(c) for c in costs[i][keep]],
+                                  "rest": int(rest[i])}
+            out.append(tree.to_nested(payload))
+        return out
+
+
+def leaf_cost_lists(tree, X, cost):
+    """Per leaf of `tree`: the FOREST_KEEP variants with the lowest mean cost over the rows of X (with their
+    multiplicity) that end in the leaf, ordered by (mean cost, id), and the mean cost of the next one."""
+    n_nodes, V = len(tree.n), cost.shape[1]
+    keep = min(FOREST_KEEP, V)
+    leaf = tree.apply(X)
+    sums = np.zeros((n_nodes, V), dtype=np.int64)
+    cnt = np.zeros(n_nodes, dtype=np.int64)
+    np.add.at(sums, leaf, np.minimum(cost, COST_CAP))
+    np.add.at(cnt, leaf, 1)
+    mean = sums // np.maximum(cnt, 1)[:, None]
+    order = np.argsort(mean, axis=1, kind="stable")  # stable: equal means stay in id order
+    ids = np.full((n_nodes, FOREST_KEEP), -1, dtype=np.int64)
+    costs = np.zeros((n_nodes, FOREST_KEEP), dtype=np.int64)
+    ids[:, :keep] = order[:, :keep]
+    costs[:, :keep] = np.take_along_axis(mean, order[:, :keep], axis=1)
+    rest = np.take_along_axis(mean, order[:, [keep if keep < V else V - 1]], axis=1)[:, 0]
+    return ids, costs, rest
+
+
+def fit_forest(X, times, bootstrap, H=None, L=4, leaf_rule="logratio", fallback=0):
+    """One tree per entry of `bootstrap` (arrays of row indices into X, drawn with replacement by the caller)."""
+    X = expand_features(X)
+    T = np.asarray(times, dtype=np.float64)
+    cost = regret_costs(T, fallback)
+    trees, ids, costs, rest = [], [], [], []
+    for idx in bootstrap:
+        idx = np.asarray(idx, dtype=np.int64)
+        tree = fit_cart(X[idx], T[idx], H, L, leaf_rule, fallback)
+        i, c, r = leaf_cost_lists(tree, X[idx], cost[idx])
+        trees.append(tree), ids.append(i), costs.append(c), rest.append(r)
+    return Forest(trees, ids, costs, rest, T.shape[1])
+
+
+def cross_validate_forest(X, T, bootstrap_for, H, L, leaf_rule, fallback=0, folds=5):
+    """As cross_validate, for a forest; `bootstrap_for(n)` returns the bootstrap index arrays for n training rows."""
+    X = np.asarray(X, dtype=np.int64)
+    T = np.asarray(T, dtype=np.float64)
+    n = X.shape[0]
+    edges = np.linspace(0, n, folds + 1).astype(int)
+    logs = []
+    for k in range(folds):
+        test = np.arange(edges[k], edges[k + 1])
+        train = np.concatenate([np.arange(0, edges[k]), np.arange(edges[k + 1], n)])
+        forest = fit_forest(X[train], T[train], bootstrap_for(train.size), H, L, leaf_rule, fallback)
+        logs.append(np.log(ratios(T[test], forest.predict(X[test]), fallback)))
+    return float(np.exp(np.mean(np.concatenate(logs))))

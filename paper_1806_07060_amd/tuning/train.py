@@ -103,6 +103,9 @@ def main(argv=None):
     ap.add_argument("--exclude", nargs="*", default=["timings_cfg1.csv", "timings_cfg2.csv", "timings_cfg3.csv"],
                     help="tables whose shapes must stay out of the training set")
     ap.add_argument("--folds", type=int, default=5)
+    ap.add_argument("--forest-trees", type=int, default=12,
+                    help="also cross-validate a forest of this many bagged trees with the chosen (H, L, leaf rule) and "
+                         "ship it instead of the single tree if it scores higher (0 = single tree only)")
     ap.add_argument("--no-write", action="store_true")
     args = ap.parse_args(argv)
 
@@ -145,6 +148,23 @@ def main(argv=None):
     print(f"held-out: accuracy {100 * held['accuracy']:.1f}%  DTPR {held['dtpr']:.4f}  geomean {held['geomean']:.4f}  "
           f"leaves {st['leaves']} height {st['height']}")
 
+    # forest of bagged trees with the same hyper-parameters: shipped only if cross-validation prefers it
+    forest, forest_cv, forest_held = None, None, None
+    if args.forest_trees > 0:
+        from .. import workloads as wl
+        boot_for = lambda n: wl.bootstrap_indices(n, args.forest_trees)  # noqa: E731
+        forest_cv = cart.cross_validate_forest(Xtr, Ttr, boot_for, best["H"], best["L"], best["leaf_rule"], links, args.folds)
+        cand = cart.fit_forest(Xtr, Ttr, boot_for(Xtr.shape[0]), best["H"], best["L"], best["leaf_rule"], links)
+        fpred = cand.predict(Xte)
+        forest_held = {"accuracy": cart.accuracy(fpred, cart.labels_from_table(Tte)), "dtpr": cart.dtpr(Tte, fpred, links),
+                       "geomean": cart.geomean_ratio(Tte, fpred, links)}
+        fst = cand.stats()
+        print(f"forest of {args.forest_trees} trees: cv geomean {forest_cv:.4f} (single tree {best['cv_geomean']:.4f}); "
+              f"held-out accuracy {100 * forest_held['accuracy']:.1f}%  DTPR {forest_held['dtpr']:.4f}  "
+              f"geomean {forest_held['geomean']:.4f}  leaves {fst['leaves']}")
+        if forest_cv > best["cv_geomean"]:
+            forest = cand
+
     d_tiled, d_direct, d_thr = (meta[0]["id"], 0, 512.0 ** 3)
     if os.path.exists(args.cfg1):
         d_tiled, d_direct, d_thr = default_dispatch(load_table(args.cfg1), meta)
@@ -153,17 +173,25 @@ def main(argv=None):
     if not args.no_write:
         name = f"{best['name']}/{best['leaf_rule']}"
         nested = tree.to_nested()
-        codegen.write_header(nested, name, variant_names=tab["variants"], default_tiled=d_tiled, default_direct=d_direct,
-                             default_threshold=d_thr,
+        forest_nested = forest.to_nested() if forest is not None else None
+        if forest is not None:
+            name = f"forest{args.forest_trees}-{name}"
+            st_ship = forest.stats()
+        else:
+            st_ship = st
+        codegen.write_header(forest_nested if forest is not None else nested, name, variant_names=tab["variants"],
+                             default_tiled=d_tiled, default_direct=d_direct, default_threshold=d_thr,
                              provenance=f"model {name}, trained on {Xtr.shape[0]} inputs ("
                                         + ", ".join(f"{src.count(n)} {n}" for n in dict.fromkeys(sorted(src))) + "); "
-                                        f"{st['leaves']} leaves, height {st['height']}")
+                                        f"{st_ship['leaves']} leaves, height {st_ship['height']}")
         os.makedirs(RESULTS, exist_ok=True)
         with open(os.path.join(RESULTS, "model.json"), "w") as f:
             json.dump({"name": name, "H": best["H"], "L": best["L"], "leaf_rule": best["leaf_rule"],
                        "training_set": {n: src.count(n) for n in dict.fromkeys(sorted(src))},
                        "cv_geomean": best["cv_geomean"], "heldout_at_training_time": held, "stats": st,
-                       "variants": tab["variants"], "tree": nested,
+                       "variants": tab["variants"], "tree": nested, "forest": forest_nested,
+                       "forest_trees": args.forest_trees if forest is not None else 0,
+                       "forest_cv_geomean": forest_cv, "forest_heldout_at_training_time": forest_held,
                        "default_dispatch": {"tiled": d_tiled, "direct": d_direct, "threshold": d_thr},
                        "sweep_on_heldout": report,
                        "cv_table": cv_table}, f, indent=1)

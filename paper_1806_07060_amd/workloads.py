@@ -358,6 +358,13 @@ def config_large_grid(values=(2048, 3072, 4096, 6144, 8192, 12288), max_flops=2.
     return _dress(triples, 9, "large")
 
 
+def bootstrap_indices(n_rows, n_trees, stream=0):
+    """Seeded bootstrap samples for a forest of decision trees: n_trees arrays of n_rows row indices drawn with
+    replacement.  Inputs of the training code and of the oracle alike (neither draws random numbers itself)."""
+    return [np.random.Generator(np.random.PCG64(case_seed(20 + stream, t))).integers(0, n_rows, n_rows)
+            for t in range(n_trees)]
+
+
 # ------------------------------------------------------------------------------------------
 # synthetic timing tables for selector tests (no GPU involved)
 # ------------------------------------------------------------------------------------------

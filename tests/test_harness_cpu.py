@@ -82,3 +82,25 @@ def test_every_configuration_index_yields_resolved_column_major_cases():
     assert len(harness.cases_for(5)) == 3375
     with pytest.raises(ValueError):
         harness.cases_for(99)
+
+
+def test_training_set_generators_are_seeded_capped_and_cover_their_corners():
+    # sizes and caps of the synthetic training sets the tuning run measures (recipes, not measured data)
+    thin, flat = wl.config_thin(), wl.config_flat()
+    assert len(thin) == 1000 and len(flat) == 1200
+    assert all(1 <= c.N <= 64 and 256 <= c.M <= 16384 and 256 <= c.K <= 8192 for c in thin)
+    assert all(16 <= c.M <= 512 and 1024 <= c.N <= 65536 and 16 <= c.K <= 4096 for c in flat)
+    tg, fg = wl.config_thin_grid(), wl.config_flat_grid()
+    assert (len(tg), len(fg)) == (1144, 1302)
+    grid = wl._geometric_grid(16, 128)
+    assert grid == [16, 24, 32, 48, 64, 96, 128]
+    assert {c.N for c in tg} == {1, 2, 4, 8, 16, 32, 64, 128} and {c.M for c in fg} == {16, 32, 64, 128, 256, 512}
+    for cases in (thin, flat, tg, fg):
+        assert all(2 * c.M * c.N * c.K <= 2 ** 38 and 4 * max(c.M * c.K, c.K * c.N, c.M * c.N) <= 6e8 for c in cases)
+        assert len({c.name for c in cases}) == len({(c.M, c.N, c.K) for c in cases})
+    # prefix-stable: a longer sweep starts with the shorter one (tables are extended, never re-measured)
+    assert [(c.M, c.N, c.K, c.transA, c.alpha) for c in wl.config_thin(50)] == [(c.M, c.N, c.K, c.transA, c.alpha) for c in thin[:50]]
+    # seeded: two calls give the same cases
+    assert [(c.M, c.N, c.K, c.transA, c.transB, c.alpha, c.beta) for c in wl.config_flat_grid()] == \
+        [(c.M, c.N, c.K, c.transA, c.transB, c.alpha, c.beta) for c in fg]
+    assert harness.cases_for(12)[0].name == tg[0].name and harness.cases_for(13)[-1].name == fg[-1].name

@@ -3,6 +3,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_1806_07060_amd import binding as mdg
@@ -136,3 +137,21 @@ def test_selectors_return_valid_ids_everywhere():
                         assert 0 <= mdg.mdg_select_default(tA, tB, M, N, K) < n
     ns = mdg.mdg_time_select_ns([0, 1], [1, 0], [64, 4096], [64, 4096], [64, 4096], iters=1000)
     assert 0 < ns < 1e5
+
+
+def test_the_memo_in_front_of_the_model_returns_what_the_model_returns():
+    # mdg_sgemm asks mdg_select_memo; it must agree with the model for fresh shapes, repeated shapes and shapes
+    # that push each other out of the 1024-entry table
+    rng = np.random.default_rng(31)
+    shapes = np.column_stack([np.rint(2.0 ** (13 * rng.uniform(size=(3000, 3)))).astype(np.int64),
+                              rng.integers(0, 2, size=(3000, 2))])
+    order = np.concatenate([np.arange(3000), rng.integers(0, 3000, 6000), np.repeat(np.arange(40), 5)])
+    for i in order:
+        M, N, K, tA, tB = (int(x) for x in shapes[i])
+        assert mdg.mdg_select_memo(tA, tB, M, N, K) == mdg.mdg_select(tA, tB, M, N, K)
+    # same sizes, different transposes are different keys
+    for tA in (0, 1):
+        for tB in (0, 1):
+            assert mdg.mdg_select_memo(tA, tB, 777, 33, 2049) == mdg.mdg_select(tA, tB, 777, 33, 2049)
+    X = shapes[:64]
+    assert mdg.mdg_time_select_ns(X[:, 3], X[:, 4], X[:, 0], X[:, 1], X[:, 2], iters=3, memo=True) > 0

@@ -298,3 +298,50 @@ def test_fallback_links_are_followed_to_the_first_legal_variant():
     assert so.effective_time(row, 3, 0) == 8.0
     with pytest.raises(ValueError):
         so.effective_time([inf, inf], 1, [0, 0])
+
+
+def test_forest_leaf_cost_lists_and_vote_by_hand(monkeypatch):
+    # one feature, two variants plus a third that is never good; times chosen so that the costs are round numbers:
+    # ratio 1 -> cost 0, ratio 1/e -> cost 2^20, ratio 1/e^2 -> cost 2^21
+    e = math.e
+    X = [so.expand_features((m, 1, 1, 0, 0)) for m in (10, 20, 30, 40)]
+    T = [[1.0, e, e * e], [1.0, e, e * e], [e, 1.0, e * e], [e * e, 1.0, e]]
+    y = so.labels_from_table(T)
+    assert y == [0, 0, 1, 1]
+    cost = so.regret_cost_rows(T)
+    S = so.REGRET_SCALE
+    assert cost == [[0, S, 2 * S], [0, S, 2 * S], [S, 0, 2 * S], [2 * S, 0, S]]
+    monkeypatch.setattr(so, "FOREST_KEEP", 2)
+    # tree 0 sees rows (0, 1, 2, 3): one split at M <= 25, pure leaves.  left leaf: means (0, S, 2S) -> keeps variants
+    # 0 and 1, rest = 2S; right leaf: sums (3S, 0, 3S) over 2 rows -> means (3S//2, 0, 3S//2) -> keeps 1 then 0
+    # (equal means: lower id first), rest = 3S//2
+    # tree 1 sees rows (0, 0, 2, 2): split at M <= 20; left leaf (row 0 twice): (0, S, 2S); right leaf (row 2 twice): (S, 0, 2S)
+    forest = so.fit_forest(X, y, T, [[0, 1, 2, 3], [0, 0, 2, 2]], None, 1, "majority", 0)
+    t0, t1 = forest
+    assert (t0["feature"], t0["threshold"]) == (0, 25) and (t1["feature"], t1["threshold"]) == (0, 20)
+    assert (t0["left"]["ids"], t0["left"]["costs"], t0["left"]["rest"]) == ([0, 1], [0, S], 2 * S)
+    assert (t0["right"]["ids"], t0["right"]["costs"], t0["right"]["rest"]) == ([1, 0], [0, 3 * S // 2], 3 * S // 2)
+    assert (t1["left"]["ids"], t1["left"]["costs"], t1["left"]["rest"]) == ([0, 1], [0, S], 2 * S)
+    assert (t1["right"]["ids"], t1["right"]["costs"], t1["right"]["rest"]) == ([1, 0], [0, S], 2 * S)
+    # M = 22: tree 0 goes left (22 <= 25), tree 1 goes right (22 > 20):
+    # variant 0: 0 + S, variant 1: S + 0, variant 2: rest 2S + rest 2S -> tie between 0 and 1 -> lowest id
+    x = so.expand_features((22, 1, 1, 0, 0))
+    assert so.forest_scores(forest, x, 3) == [S, S, 4 * S]
+    assert so.predict_forest(forest, x, 3) == 0
+    # M = 35: both right: variant 0: 3S//2 + S, variant 1: 0, variant 2: 3S//2 + 2S
+    x = so.expand_features((35, 1, 1, 0, 0))
+    assert so.forest_scores(forest, x, 3) == [3 * S // 2 + S, 0, 3 * S // 2 + 2 * S]
+    assert so.predict_forest(forest, x, 3) == 1
+
+
+def test_forest_of_identical_full_samples_predicts_like_its_tree_when_leaves_are_pure():
+    # bootstrap = the whole training set, fully grown tree, distinct inputs: every leaf holds one input, whose
+    # best variant has cost 0 -> the forest (any number of copies) reproduces the labels
+    rows = [(m, n, 3, 0, 0) for m in (1, 5, 9, 13) for n in (2, 4, 8)]
+    X = [so.expand_features(r) for r in rows]
+    T = [[1.0 + ((3 * i + 2 * v) % 7) for v in range(5)] for i in range(len(rows))]
+    y = so.labels_from_table(T)
+    whole = list(range(len(rows)))
+    forest = so.fit_forest(X, y, T, [whole, whole, whole], None, 1, "majority", 0)
+    assert [so.predict_forest(forest, x, 5) for x in X] == y
+    assert so.geomean_ratio(T, [so.predict_forest(forest, x, 5) for x in X]) == 1.0

@@ -31,8 +31,11 @@ def _probe(feature, value, base=(64, 64, 64, 0, 1)):
         p[feature] = value
     elif feature == 5:
         p[0], p[1] = value, 1
-    else:
+    elif feature == 6:
         p[0], p[1], p[2] = value, 1, 1
+    else:  # tile-fit features: padM32/64/128 (7-9), padN32/64/128 (10-12) = (t - X mod t) mod t
+        t = (32, 64, 128)[(feature - 7) % 3]
+        p[0 if feature < 10 else 1] = 3 * t - (value % t)
     return tuple(p)
 
 
@@ -147,6 +150,36 @@ def test_generated_cpp_equals_the_tree_everywhere(H, L, rule, tmp_path):
     assert lib.sel(0, 0, big[0], big[1], big[2]) == so.predict(nested, so.expand_features(big)) == int(tree.predict([big])[0])
 
 
+@pytest.mark.parametrize("seed,n,v,trees", [(7, 220, 9, 3), (8, 300, 12, 5)])
+def test_forest_is_identical_to_the_oracle_and_to_its_generated_code(seed, n, v, trees, tmp_path):
+    X, T, Xl, Tl = _table(n, v, seed)
+    ntr = n - 60
+    boot = wl.bootstrap_indices(ntr, trees)
+    assert len(boot) == trees and all(b.shape == (ntr,) and b.min() >= 0 and b.max() < ntr for b in boot)
+    assert all(np.array_equal(a, b) for a, b in zip(boot, wl.bootstrap_indices(ntr, trees)))  # seeded
+    y = so.labels_from_table(Tl[:ntr])
+    for rule, H, L in (("logratio", None, 4), ("majority", 3, 2)):
+        ours = cart.fit_forest(X[:ntr], T[:ntr], boot, H, L, rule, 0)
+        ref = so.fit_forest(Xl[:ntr], y, Tl[:ntr], [b.tolist() for b in boot], H, L, rule, 0)
+        nested = ours.to_nested()
+        assert nested == ref, rule
+        want = ours.predict(X)
+        assert want.tolist() == [so.predict_forest(ref, x, v) for x in Xl]
+        assert ours.scores(X[:20]).tolist() == [so.forest_scores(ref, x, v) for x in Xl[:20]]
+        text = codegen.tree_to_cpp(nested, "test-forest", variant_names=[f"v{i}" for i in range(v)])
+        sub = tmp_path / rule  # a fresh path per library: the loader would hand back the first one otherwise
+        sub.mkdir()
+        lib = _compile_selector(text, sub)
+        probes = [tuple(r) for r in X.tolist()]
+        for f, thr in codegen.internal_thresholds(nested):
+            for d in (-1, 0, 1):
+                probes.append(_probe(f, max(thr + d, 0), base=tuple(X[0].tolist())))
+        P = np.array(probes, dtype=np.int64)
+        got = [lib.sel(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) for p in P]
+        assert got == ours.predict(P).tolist()
+        assert got == [so.predict_forest(ref, so.expand_features(tuple(int(x) for x in p)), v) for p in P]
+
+
 def test_shipped_selector_matches_the_stored_model():
     # the header compiled into the library must be the one generated from results/model.json
     from paper_1806_07060_amd import binding as mdg
@@ -160,13 +193,19 @@ def test_shipped_selector_matches_the_stored_model():
     P = np.column_stack([np.rint(2.0 ** (13 * rng.uniform(size=(3000, 3)))).astype(np.int64),
                          rng.integers(0, 2, size=(3000, 2))])
     extra = []
-    for f, thr in codegen.internal_thresholds(model["tree"]):
+    shipped = model.get("forest") or model["tree"]  # a list of trees with cost lists, or one tree
+    n_var = len(model["variants"])
+    thresholds = codegen.internal_thresholds(shipped)
+    if len(thresholds) > 4000:  # a forest has tens of thousands of nodes: probe a seeded sample of them
+        thresholds = [thresholds[i] for i in rng.choice(len(thresholds), 4000, replace=False)]
+    for f, thr in thresholds:
         for d in (-1, 0, 1):
             extra.append(_probe(f, max(0, thr + d)))
     P = np.vstack([P, np.array(extra, dtype=np.int64).reshape(-1, 5)])
     for p in P:
-        assert mdg.mdg_select(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) == \
-            so.predict(model["tree"], so.expand_features(tuple(int(x) for x in p)))
+        x = so.expand_features(tuple(int(a) for a in p))
+        want = so.predict_forest(shipped, x, n_var) if isinstance(shipped, list) else so.predict(shipped, x)
+        assert mdg.mdg_select(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) == want
     d = model["default_dispatch"]
     assert mdg.mdg_select_default(0, 0, 4096, 4096, 4096) == d["tiled"]
     assert mdg.mdg_select_default(0, 0, 8, 8, 8) == d["direct"]
