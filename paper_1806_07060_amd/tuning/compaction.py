@@ -5,8 +5,9 @@ almost as well as a 3375-point one inside its own range.)
   python -m paper_1806_07060_amd.tuning.compaction
 
 The training union is already in seeded random order, so a prefix of it is a uniform subsample of every
-generation rule at once.  For each fraction the shipped model family member (same H, L and leaf rule as the
-compiled selector, read from results/model.json) is trained on that prefix and scored on the usual test sets:
+generation rule at once.  For each fraction one tree with the shipped hyper-parameters (H, L and leaf rule
+read from results/model.json; a single tree also when the shipped selector is a forest of such trees) is
+trained on that prefix and scored on the usual test sets:
 the held-out 20 % of the random sweep and the square / skinny / convolution-lowered sets no training set
 contains.  Also reports what the prefix cost to measure: the sum of the recorded times of every legal variant
 on its inputs (one call each; the tuning run spends a small multiple of that).  Writes results/compaction.json.
@@ -47,8 +48,9 @@ def main():
 
     from .. import binding as mdg
     links = [int(v["fallback"]) for v in mdg.variants()]
-    out = {"model": model["name"], "rows": []}
-    print(f"model {model['name']}; full training set {X.shape[0]} inputs")
+    name = f"{cart.model_name(H, L)}/{rule}"  # one tree with the shipped hyper-parameters, also when a forest ships
+    out = {"model": name, "rows": []}
+    print(f"model {name} (single tree); full training set {X.shape[0]} inputs")
     print(f"{'fraction':>9s} {'inputs':>6s} {'leaves':>6s} {'one pass s':>10s} " + " ".join(f"{k[:20]:>20s}" for k in tests))
     for frac in FRACTIONS:
         n = max(8, int(round(frac * X.shape[0])))
