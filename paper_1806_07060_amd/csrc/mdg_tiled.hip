@@ -25,9 +25,9 @@
 //
 // LDS: two stages of As[BK][BM + 4] and Bs[BK][BN + 4] (k-major rows, the
 // non-contracted index contiguous).  Global loads are float4 along whichever
-// index is contiguous in memory; operands stored with k contiguous are
-// transposed on their way into LDS (four 4-byte writes; the +4 padding spreads
-// them over the banks).  One barrier per K step; global loads run two K steps
+// index is contiguous in memory (also for operands that are only 4-byte
+// aligned); operands stored with k contiguous are transposed on their way into
+// LDS (four 4-byte writes; the +4 padding spreads them over the banks).  One barrier per K step; global loads run two K steps
 // ahead (two register sets), LDS stages alternate.
 #include <type_traits>
 
@@ -39,6 +39,40 @@ namespace mdg {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+// Four consecutive floats at an address that is only 4-byte aligned (odd leading dimensions, offset base
+// pointers).  The compiler turns a load through this type into one 16-byte load as well: global memory accepts
+// any dword-aligned address for it.
+typedef floatx4 floatx4u __attribute__((aligned(4)));
+typedef floatx2 floatx2u __attribute__((aligned(4)));
+
+// F consecutive floats of C (or of the split-K workspace) as one access; `aligned` says whether the address is
+// a multiple of 4 * F bytes, otherwise the 4-byte-aligned vector types are used.
+template <int F>
+__device__ __forceinline__ void load_run(float (&dst)[F], const float* src, bool aligned) {
+  if constexpr (F == 4) {
+    const floatx4 v = aligned ? *reinterpret_cast<const floatx4*>(src) : floatx4(*reinterpret_cast<const floatx4u*>(src));
+    dst[0] = v[0], dst[1] = v[1], dst[2] = v[2], dst[3] = v[3];
+  } else if constexpr (F == 2) {
+    const floatx2 v = aligned ? *reinterpret_cast<const floatx2*>(src) : floatx2(*reinterpret_cast<const floatx2u*>(src));
+    dst[0] = v[0], dst[1] = v[1];
+  } else {
+    dst[0] = *src;
+  }
+}
+template <int F>
+__device__ __forceinline__ void store_run(float* dst, const float (&v)[F], bool aligned) {
+  if constexpr (F == 4) {
+    const floatx4 o = {v[0], v[1], v[2], v[3]};
+    if (aligned) *reinterpret_cast<floatx4*>(dst) = o;
+    else *reinterpret_cast<floatx4u*>(dst) = o;
+  } else if constexpr (F == 2) {
+    const floatx2 o = {v[0], v[1]};
+    if (aligned) *reinterpret_cast<floatx2*>(dst) = o;
+    else *reinterpret_cast<floatx2u*>(dst) = o;
+  } else {
+    dst[0] = v[0];
+  }
+}
 
 struct TiledParams {
   const float* A;
@@ -58,7 +92,8 @@ constexpr int kGroupM = 8;  // tiles per group along M in the tile ordering
 
 // Loads one BMN x BK operand tile into registers (float4 slots).
 //   KMAJOR = stored with k contiguous:  X[k + mn * ld]   else   X[mn + k * ld]
-// `fast` (work-group uniform) = whole tile in range and vector loads aligned.
+// `inside` (work-group uniform) = whole tile in range: 16-byte loads, through the aligned or the 4-byte-aligned
+// vector type (`aligned`, uniform too); otherwise element-wise guarded loads.
 template <int BMN, int BK, int NT, bool KMAJOR>
 struct OperandLoader {
   static constexpr int kSlots = BMN * BK / 4 / NT;
@@ -82,16 +117,23 @@ struct OperandLoader {
   }
 
   __device__ __forceinline__ static void load(floatx4 (&r)[kSlots], const float* __restrict__ X, int64_t ld, int mn0,
-                                              int k0, int mn_lim, int k_lim, bool fast, int tid) {
-    if (fast) {
+                                              int k0, int mn_lim, int k_lim, bool inside, bool aligned, int tid) {
+    if (inside) {
+      const float* src[kSlots];
 #pragma unroll
       for (int s = 0; s < kSlots; ++s) {
         int mn, k;
         coords(s, tid, mn, k);
         mn += mn0;
         k += k0;
-        const float* src = KMAJOR ? X + (int64_t)k + (int64_t)mn * ld : X + (int64_t)mn + (int64_t)k * ld;
-        r[s] = *reinterpret_cast<const floatx4*>(src);
+        src[s] = KMAJOR ? X + (int64_t)k + (int64_t)mn * ld : X + (int64_t)mn + (int64_t)k * ld;
+      }
+      if (aligned) {
+#pragma unroll
+        for (int s = 0; s < kSlots; ++s) r[s] = *reinterpret_cast<const floatx4*>(src[s]);
+      } else {
+#pragma unroll
+        for (int s = 0; s < kSlots; ++s) r[s] = *reinterpret_cast<const floatx4u*>(src[s]);
       }
     } else {
 #pragma unroll
@@ -132,9 +174,13 @@ struct OperandLoader {
     return reinterpret_cast<const char*>(KMAJOR ? X + (int64_t)k0 + (int64_t)mn0 * ld : X + (int64_t)mn0 + (int64_t)k0 * ld);
   }
   __device__ __forceinline__ static int64_t fast_stride(int64_t ld) { return KMAJOR ? (int64_t)BK * 4 : (int64_t)BK * ld * 4; }
+  template <bool ALIGNED>
   __device__ __forceinline__ static void fast_load(floatx4 (&r)[kSlots], const char* base, const uint32_t (&off)[kSlots]) {
 #pragma unroll
-    for (int s = 0; s < kSlots; ++s) r[s] = *reinterpret_cast<const floatx4*>(base + off[s]);
+    for (int s = 0; s < kSlots; ++s) {
+      if constexpr (ALIGNED) r[s] = *reinterpret_cast<const floatx4*>(base + off[s]);
+      else r[s] = *reinterpret_cast<const floatx4u*>(base + off[s]);
+    }
   }
 
   // registers -> LDS stage S[BK][BMN + kPad]
@@ -225,8 +271,8 @@ void tiled_kernel(TiledParams p) {
   const int k_end = min(p.K, k_begin + p.k_per_split);
   const int n_steps = (k_end - k_begin + BK - 1) / BK;
 
-  const bool a_full = p.a_vec && (m0 + BM <= p.M);
-  const bool b_full = p.b_vec && (n0 + BN <= p.N);
+  const bool a_full = (m0 + BM <= p.M), b_full = (n0 + BN <= p.N);  // tile inside the operand along m / n
+  const bool a_al = p.a_vec != 0, b_al = p.b_vec != 0;              // 16-byte loads of that operand are aligned
 
   floatx16 acc[FN][FM];
 #pragma unroll
@@ -250,8 +296,8 @@ void tiled_kernel(TiledParams p) {
     if (ti < n_steps) {
       const int k0 = k_begin + ti * BK;
       const bool kfull = (k0 + BK <= k_end);
-      LoadA::load(qa, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, tid);
-      LoadB::load(qb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, tid);
+      LoadA::load(qa, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, a_al, tid);
+      LoadB::load(qb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, b_al, tid);
     }
   };
 
@@ -308,7 +354,8 @@ void tiled_kernel(TiledParams p) {
   using Buf1 = std::integral_constant<int, 1>;
 
   int t = 0;
-  // ---- interior tiles: K steps whose second successor is a full, aligned tile use the lean loads
+  // ---- interior tiles: K steps whose second successor is a full tile use the lean loads (one instance of the
+  // loop for aligned operands, one that goes through the 4-byte-aligned vector type for everything else)
   const int n_full = (a_full && b_full && LoadA::offsets_fit(p.lda) && LoadB::offsets_fit(p.ldb))
                          ? (k_end - k_begin) / BK : 0;
   if (n_full > NS + 1) {
@@ -318,16 +365,21 @@ void tiled_kernel(TiledParams p) {
     const char* pa = LoadA::fast_base(p.A, p.lda, m0, k_begin + NS * BK);
     const char* pb = LoadB::fast_base(p.B, p.ldb, n0, k_begin + NS * BK);
     const int64_t sa = LoadA::fast_stride(p.lda), sb = LoadB::fast_stride(p.ldb);
-    auto lean = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots]) __attribute__((always_inline)) {
-      LoadA::fast_load(qa, pa, offa);
-      LoadB::fast_load(qb, pb, offb);
-      pa += sa;
-      pb += sb;
+    auto interior = [&](auto aligned_tag) __attribute__((always_inline)) {
+      constexpr bool AL = decltype(aligned_tag)::value;
+      auto lean = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots]) __attribute__((always_inline)) {
+        LoadA::template fast_load<AL>(qa, pa, offa);
+        LoadB::template fast_load<AL>(qb, pb, offb);
+        pa += sa;
+        pb += sb;
+      };
+      for (; t + NS + 1 < n_full; t += 2) {  // loads tiles t+NS and t+NS+1, both full
+        k_step(Buf0{}, lean, true);
+        k_step(Buf1{}, lean, true);
+      }
     };
-    for (; t + NS + 1 < n_full; t += 2) {  // loads tiles t+NS and t+NS+1, both full
-      k_step(Buf0{}, lean, true);
-      k_step(Buf1{}, lean, true);
-    }
+    if (a_al && b_al) interior(std::true_type{});
+    else interior(std::false_type{});
   }
   // ---- everything else (edge tiles, unaligned operands, the K tail): guarded loads
   for (; t < n_steps; ++t) {
@@ -371,7 +423,8 @@ void tiled_kernel(TiledParams p) {
   if (p.split_k > 1) {
     // raw partial sums into slice `split` of the workspace (tight column-major M x N)
     float* W = p.ws + (int64_t)split * p.M * p.N;
-    const bool vec = (FM > 1) && ((p.M & 3) == 0) && (m_base + FM <= p.M);
+    const bool vec = (FM > 1) && (m_base + FM <= p.M);  // the lane's FM rows are all inside
+    const bool w_al = (p.M & 3) == 0;                    // slices are 256-byte aligned, columns M floats apart
 #pragma unroll
     for (int c = 0; c < FN; ++c)
 #pragma unroll
@@ -380,13 +433,10 @@ void tiled_kernel(TiledParams p) {
         if (n >= p.N) continue;
         float* dst = W + (int64_t)m_base + (int64_t)n * p.M;
         if (vec) {
-          if constexpr (FM == 4) {
-            floatx4 o = {acc[c][0][r], acc[c][1][r], acc[c][2][r], acc[c][3][r]};
-            *reinterpret_cast<floatx4*>(dst) = o;
-          } else if constexpr (FM == 2) {
-            floatx2 o = {acc[c][0][r], acc[c][1][r]};
-            *reinterpret_cast<floatx2*>(dst) = o;
-          }
+          float o[FM];
+#pragma unroll
+          for (int b = 0; b < FM; ++b) o[b] = acc[c][b][r];
+          store_run<FM>(dst, o, w_al);
         } else {
 #pragma unroll
           for (int b = 0; b < FM; ++b)
@@ -397,7 +447,7 @@ void tiled_kernel(TiledParams p) {
   }
 
   const bool c_al = ((p.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
-  const bool vec = (FM > 1) && c_al && (m_base + FM <= p.M);
+  const bool vec = (FM > 1) && (m_base + FM <= p.M);  // the lane's FM rows are all inside
   const float alpha = p.alpha, beta = p.beta;
   // Per block column c: first all reads of the old C (16 independent loads in flight per lane --
   // read-then-write one row at a time would pay the memory latency sixteen times), then scale and store.
@@ -410,13 +460,7 @@ void tiled_kernel(TiledParams p) {
         const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
         const float* src = p.C + (int64_t)m_base + (int64_t)min(n, p.N - 1) * p.ldc;
         if (vec) {
-          if constexpr (FM == 4) {
-            const floatx4 v = *reinterpret_cast<const floatx4*>(src);
-            old[r][0] = v[0], old[r][1] = v[1], old[r][2] = v[2], old[r][3] = v[3];
-          } else if constexpr (FM == 2) {
-            const floatx2 v = *reinterpret_cast<const floatx2*>(src);
-            old[r][0] = v[0], old[r][1] = v[1];
-          }
+          load_run<FM>(old[r], src, c_al);
         } else {
 #pragma unroll
           for (int b = 0; b < FM; ++b) old[r][b] = (m_base + b < p.M) ? src[b] : 0.f;
@@ -435,13 +479,7 @@ void tiled_kernel(TiledParams p) {
         if (beta != 0.f) o[b] = fmaf(beta, old[r][b], o[b]);
       }
       if (vec) {
-        if constexpr (FM == 4) {
-          const floatx4 v = {o[0], o[1], o[2], o[3]};
-          *reinterpret_cast<floatx4*>(dst) = v;
-        } else if constexpr (FM == 2) {
-          const floatx2 v = {o[0], o[1]};
-          *reinterpret_cast<floatx2*>(dst) = v;
-        }
+        store_run<FM>(dst, o, c_al);
       } else {
 #pragma unroll
         for (int b = 0; b < FM; ++b)
