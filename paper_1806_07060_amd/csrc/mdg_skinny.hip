@@ -15,8 +15,9 @@
 //     flight; lane = row, B(k, j) is wave-uniform and read with scalar loads; the
 //     W partial sums meet in LDS and are added in wave order.
 //   A transposed (k contiguous): one wave per R = 4 rows; lanes run along k with
-//     16-byte loads when the operands are aligned (two per row in flight), scalar
-//     loads otherwise; partial dot products are combined with a cross-lane butterfly.
+//     16-byte loads (two per row in flight; any 4-byte-aligned address will do),
+//     scalar loads for the tail and for a transposed B; partial dot products are
+//     combined with a cross-lane butterfly.
 // K may additionally be cut into split_k slices (grid.y): partial sums then go to
 // the workspace and the reduce pass finishes C.  Columns beyond NB are covered by
 // blockIdx.z.  Every sum is formed in a fixed order: results are deterministic.
@@ -26,6 +27,9 @@
 namespace mdg {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+// four consecutive floats at any 4-byte-aligned address: one 16-byte load all the same (global memory takes any
+// dword-aligned address), so the vector paths below need their elements in range, not aligned
+typedef floatx4 floatx4u __attribute__((aligned(4)));
 
 struct SkinnyParams {
   const float* A;
@@ -36,7 +40,6 @@ struct SkinnyParams {
   int M, N, K;
   int split_k, k_per_split;
   float alpha, beta;
-  int vec_ok;  // A-transposed path: 16-byte loads along k are aligned for A and B
 };
 
 template <bool TB>
@@ -135,20 +138,20 @@ __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
     for (int j = 0; j < NB; ++j) acc[r][j] = 0.f;
 
   int k = k_begin;
-  if (!TB && p.vec_ok && (k_begin & 3) == 0) {
+  if (!TB) {
     // 16-byte loads: a wave covers 256 consecutive k per row and trip, two trips in flight
     for (; k + 512 <= k_end; k += 512) {
       floatx4 a0[R], a1[R];
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        a0[r] = *reinterpret_cast<const floatx4*>(arow[r] + k + 4 * lane);
-        a1[r] = *reinterpret_cast<const floatx4*>(arow[r] + k + 256 + 4 * lane);
+        a0[r] = *reinterpret_cast<const floatx4u*>(arow[r] + k + 4 * lane);
+        a1[r] = *reinterpret_cast<const floatx4u*>(arow[r] + k + 256 + 4 * lane);
       }
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
         const float* bcol = p.B + (int64_t)jc[j] * p.ldb + k + 4 * lane;
-        const floatx4 b0 = *reinterpret_cast<const floatx4*>(bcol);
-        const floatx4 b1 = *reinterpret_cast<const floatx4*>(bcol + 256);
+        const floatx4 b0 = *reinterpret_cast<const floatx4u*>(bcol);
+        const floatx4 b1 = *reinterpret_cast<const floatx4u*>(bcol + 256);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
 #pragma unroll
@@ -161,10 +164,10 @@ __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
     for (; k + 256 <= k_end; k += 256) {
       floatx4 a0[R];
 #pragma unroll
-      for (int r = 0; r < R; ++r) a0[r] = *reinterpret_cast<const floatx4*>(arow[r] + k + 4 * lane);
+      for (int r = 0; r < R; ++r) a0[r] = *reinterpret_cast<const floatx4u*>(arow[r] + k + 4 * lane);
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
-        const floatx4 b0 = *reinterpret_cast<const floatx4*>(p.B + (int64_t)jc[j] * p.ldb + k + 4 * lane);
+        const floatx4 b0 = *reinterpret_cast<const floatx4u*>(p.B + (int64_t)jc[j] * p.ldb + k + 4 * lane);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
       }
     }
   }
-  // scalar loads: unaligned operands, transposed B, and the tail of the vector path
+  // scalar loads: transposed B, and the tail of the vector path
   k += lane;
   for (; k + 64 < k_end; k += 128) {  // two k per lane per trip
     float a0[R], a1[R], b0[NB], b1[NB];
@@ -230,10 +233,11 @@ __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
 //   A transposed: lane (j, kk) loads k + 4 kk .. + 3 of row m0 + j with one 16-byte load (16 rows x 16 k);
 //     value t feeds step t, whose SrcA holds op(B)(k + 4 kk + t, n) -- any pairing of k with (step, kk)
 //     is a valid order of summation as long as both operands use the same one.
-// VEC = 16-byte loads allowed (aligned operands; for A not transposed also M % 4 == 0, so that a
-// 4-row group is inside or outside as a whole).  Rows and columns past the edge are clamped for
+// VEC = 16-byte loads allowed: always when A is transposed; when it is not, M % 4 == 0 is needed so that a
+// 4-row group is inside or outside as a whole.  Alignment is not: the loads go through floatx4u.  Rows and columns past the edge are clamped for
 // loads and skipped for stores; k past the end multiplies zeros.
 typedef float floatx4m __attribute__((ext_vector_type(4)));
+typedef floatx4m floatx4mu __attribute__((aligned(4)));
 
 template <bool TA, bool TB, int NBK, bool VEC>
 __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(SkinnyParams p) {
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
     if constexpr (TA) {
       const int k = k0 + 4 * kk;
       const float* src = p.A + (int64_t)k + (int64_t)mrow * p.lda;
-      if (VEC && !guard) return *reinterpret_cast<const floatx4m*>(src);
+      if (VEC && !guard) return *reinterpret_cast<const floatx4mu*>(src);
 #pragma unroll
       for (int t = 0; t < 4; ++t) a[t] = (k + t < kw_end) ? src[t] : 0.f;
     } else {
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
       const bool in = k < kw_end;
       const float* src = p.A + (int64_t)mrow + (int64_t)min(k, p.K - 1) * p.lda;
       if constexpr (VEC) {
-        a = *reinterpret_cast<const floatx4m*>(src);
+        a = *reinterpret_cast<const floatx4mu*>(src);
         if (guard && !in) a = floatx4m{0.f, 0.f, 0.f, 0.f};
       } else {
 #pragma unroll
@@ -295,7 +299,7 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
     floatx4m b = floatx4m{0.f, 0.f, 0.f, 0.f};
     if constexpr (TA) {
       const int k = k0 + 4 * kk;
-      if (!TB && VEC && !guard) return *reinterpret_cast<const floatx4m*>(p.B + (int64_t)k + (int64_t)ncol[nb] * p.ldb);
+      if (!TB && VEC && !guard) return *reinterpret_cast<const floatx4mu*>(p.B + (int64_t)k + (int64_t)ncol[nb] * p.ldb);
 #pragma unroll
       for (int t = 0; t < 4; ++t) b[t] = (k + t < kw_end) ? ld_b<TB>(p.B, p.ldb, k + t, ncol[nb]) : 0.f;
     } else {
@@ -372,12 +376,9 @@ static int launch_mfma_cfg(int split_k, const GemmArgs& g) {
   p.split_k = split_k;
   p.k_per_split = (int)((((g.K + split_k - 1) / split_k) + 15) / 16 * 16);  // slices start at multiples of 16
   p.alpha = g.alpha, p.beta = g.beta;
-  const bool a_al = ((g.lda & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0);
-  const bool b_al = ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
-  // 16-byte loads: along m for A not transposed (then a 4-row group must not straddle the edge),
-  // along k for A transposed (B is then read the same way when it is k-contiguous, so it must be aligned too)
-  const bool vec = g.tA ? (a_al && (g.tB || b_al)) : (a_al && (g.M & 3) == 0 && g.M >= 4);
-  p.vec_ok = vec;
+  // 16-byte loads: along k for A transposed (always possible), along m for A not transposed (then a 4-row
+  // group must not straddle the edge)
+  const bool vec = g.tA ? true : ((g.M & 3) == 0 && g.M >= 4);
   const int64_t col_groups = (g.N + 16 * NBK - 1) / (16 * NBK);
   const int64_t strips = (g.M + (g.tA ? 15 : 63)) / (g.tA ? 16 : 64);
   if (col_groups > 65535 || split_k > 65535 || strips > 0x7fffffffLL) return MDG_ERR_LAUNCH;
@@ -407,11 +408,8 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
   p.lda = g.lda, p.ldb = g.ldb, p.ldc = g.ldc;
   p.M = (int)g.M, p.N = (int)g.N, p.K = (int)g.K;
   p.split_k = split_k;
-  // slices are multiples of 4 so that the 16-byte path stays aligned in every slice
   p.k_per_split = (int)((((g.K + split_k - 1) / split_k) + 3) / 4 * 4);
   p.alpha = g.alpha, p.beta = g.beta;
-  p.vec_ok = ((g.lda & 3) == 0) && ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
-             ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
   const int64_t col_groups = (g.N + NB - 1) / NB;
   if (col_groups > 65535 || split_k > 65535) return MDG_ERR_LAUNCH;
   if (!g.tA) {
