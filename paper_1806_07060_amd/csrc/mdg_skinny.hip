@@ -236,8 +236,6 @@ __global__ __launch_bounds__(256) void skinny_t_kernel(SkinnyParams p) {
 // VEC = 16-byte loads allowed: always when A is transposed; when it is not, M % 4 == 0 is needed so that a
 // 4-row group is inside or outside as a whole.  Alignment is not: the loads go through floatx4u.  Rows and columns past the edge are clamped for
 // loads and skipped for stores; k past the end multiplies zeros.
-typedef float floatx4m __attribute__((ext_vector_type(4)));
-typedef floatx4m floatx4mu __attribute__((aligned(4)));
 
 template <bool TA, bool TB, int NBK, bool VEC>
 __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(SkinnyParams p) {
@@ -264,20 +262,20 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
   // first row this lane loads (clamped so that every load stays inside A)
   const int mrow = TA ? min(m0 + j, p.M - 1) : (VEC ? min(m0 + 4 * j, p.M - 4) : m0 + 4 * j);
 
-  floatx4m acc[NBK][MB];
+  floatx4 acc[NBK][MB];
 #pragma unroll
   for (int nb = 0; nb < NBK; ++nb)
 #pragma unroll
-    for (int b = 0; b < MB; ++b) acc[nb][b] = floatx4m{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < MB; ++b) acc[nb][b] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   // one wave load of A and the matching values of op(B), at k offset k0 of this lane's chunk; `guard`
   // (tail only) zero-fills k >= kw_end
-  auto load_a = [&](int k0, bool guard) __attribute__((always_inline)) -> floatx4m {
-    floatx4m a;
+  auto load_a = [&](int k0, bool guard) __attribute__((always_inline)) -> floatx4 {
+    floatx4 a;
     if constexpr (TA) {
       const int k = k0 + 4 * kk;
       const float* src = p.A + (int64_t)k + (int64_t)mrow * p.lda;
-      if (VEC && !guard) return *reinterpret_cast<const floatx4mu*>(src);
+      if (VEC && !guard) return *reinterpret_cast<const floatx4u*>(src);
 #pragma unroll
       for (int t = 0; t < 4; ++t) a[t] = (k + t < kw_end) ? src[t] : 0.f;
     } else {
@@ -285,8 +283,8 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
       const bool in = k < kw_end;
       const float* src = p.A + (int64_t)mrow + (int64_t)min(k, p.K - 1) * p.lda;
       if constexpr (VEC) {
-        a = *reinterpret_cast<const floatx4mu*>(src);
-        if (guard && !in) a = floatx4m{0.f, 0.f, 0.f, 0.f};
+        a = *reinterpret_cast<const floatx4u*>(src);
+        if (guard && !in) a = floatx4{0.f, 0.f, 0.f, 0.f};
       } else {
 #pragma unroll
         for (int b = 0; b < 4; ++b) a[b] = in ? src[min(mrow + b, p.M - 1) - mrow] : 0.f;
@@ -295,11 +293,11 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
     return a;
   };
   // op(B)(k, n) for the lane's k values: TA -> four consecutive k (steps t), else the single k of this lane
-  auto load_b = [&](int k0, int nb, bool guard) __attribute__((always_inline)) -> floatx4m {
-    floatx4m b = floatx4m{0.f, 0.f, 0.f, 0.f};
+  auto load_b = [&](int k0, int nb, bool guard) __attribute__((always_inline)) -> floatx4 {
+    floatx4 b = floatx4{0.f, 0.f, 0.f, 0.f};
     if constexpr (TA) {
       const int k = k0 + 4 * kk;
-      if (!TB && VEC && !guard) return *reinterpret_cast<const floatx4mu*>(p.B + (int64_t)k + (int64_t)ncol[nb] * p.ldb);
+      if (!TB && VEC && !guard) return *reinterpret_cast<const floatx4u*>(p.B + (int64_t)k + (int64_t)ncol[nb] * p.ldb);
 #pragma unroll
       for (int t = 0; t < 4; ++t) b[t] = (k + t < kw_end) ? ld_b<TB>(p.B, p.ldb, k + t, ncol[nb]) : 0.f;
     } else {
@@ -308,7 +306,7 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
     }
     return b;
   };
-  auto multiply = [&](const floatx4m& a, const floatx4m (&b)[NBK]) __attribute__((always_inline)) {
+  auto multiply = [&](const floatx4& a, const floatx4 (&b)[NBK]) __attribute__((always_inline)) {
 #pragma unroll
     for (int nb = 0; nb < NBK; ++nb) {
       if constexpr (TA) {
@@ -324,7 +322,7 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
 
   int k = kw_begin;
   for (; k + U * KU <= kw_end; k += U * KU) {
-    floatx4m av[U], bv[U][NBK];
+    floatx4 av[U], bv[U][NBK];
 #pragma unroll
     for (int u = 0; u < U; ++u) av[u] = load_a(k + u * KU, false);
 #pragma unroll
@@ -340,8 +338,8 @@ __global__ __launch_bounds__(64 * (NBK == 1 ? 16 : 8)) void thin_mfma_kernel(Ski
   }
   for (; k < kw_end; k += KU) {  // remaining wave loads one at a time; only the last can be partial
     const bool partial = k + KU > kw_end;
-    floatx4m bv[NBK];
-    const floatx4m av = load_a(k, partial);
+    floatx4 bv[NBK];
+    const floatx4 av = load_a(k, partial);
 #pragma unroll
     for (int nb = 0; nb < NBK; ++nb) bv[nb] = load_b(k, nb, partial);
     multiply(av, bv);
