@@ -136,20 +136,29 @@ struct OperandLoader {
         for (int s = 0; s < kSlots; ++s) r[s] = *reinterpret_cast<const floatx4u*>(src[s]);
       }
     } else {
+      // border tiles and the K tail: a slot whose four elements are all in range still takes one 16-byte load
+      // (most lanes of a border tile); only the slots that straddle or lie past an edge go element by element.
+      // Nothing outside the logical matrix is ever read.
 #pragma unroll
       for (int s = 0; s < kSlots; ++s) {
         int mn, k;
         coords(s, tid, mn, k);
         mn += mn0;
         k += k0;
+        const bool whole = KMAJOR ? (mn < mn_lim && k + 3 < k_lim) : (k < k_lim && mn + 3 < mn_lim);
         floatx4 v;
+        if (whole) {
+          v = *reinterpret_cast<const floatx4u*>(KMAJOR ? X + (int64_t)k + (int64_t)mn * ld
+                                                        : X + (int64_t)mn + (int64_t)k * ld);
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          int mm = KMAJOR ? mn : mn + e;
-          int kk = KMAJOR ? k + e : k;
-          float x = 0.f;
-          if (mm < mn_lim && kk < k_lim) x = KMAJOR ? X[(int64_t)kk + (int64_t)mm * ld] : X[(int64_t)mm + (int64_t)kk * ld];
-          v[e] = x;
+          for (int e = 0; e < 4; ++e) {
+            int mm = KMAJOR ? mn : mn + e;
+            int kk = KMAJOR ? k + e : k;
+            float x = 0.f;
+            if (mm < mn_lim && kk < k_lim) x = KMAJOR ? X[(int64_t)kk + (int64_t)mm * ld] : X[(int64_t)mm + (int64_t)kk * ld];
+            v[e] = x;
+          }
         }
         r[s] = v;
       }
