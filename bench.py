@@ -93,8 +93,8 @@ def main():
                          "are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; --gpus must be 1 (the sharding design is described in "
-              "DESIGN.md, nothing here uses a second GPU)", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (a call shards over GPUs by column blocks "
+              "of B and C without communication, but nothing here uses a second GPU)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

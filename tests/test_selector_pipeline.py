@@ -242,7 +242,7 @@ def test_default_dispatch_picks_per_family_bests_on_the_two_cubes():
 
 
 def test_product_and_oracle_agree_on_measured_tables():
-    # the same trees on a slice of the real timing table (illegal entries, fallback links, 52 classes)
+    # the same trees on a slice of the real timing table (illegal entries, fallback links, dozens of classes)
     from paper_1806_07060_amd import binding as mdg
     from paper_1806_07060_amd.tuning import train
     path = os.path.join(train.RESULTS, "timings_cfg4.csv")
