@@ -180,6 +180,30 @@ def test_forest_is_identical_to_the_oracle_and_to_its_generated_code(seed, n, v,
         assert got == [so.predict_forest(ref, so.expand_features(tuple(int(x) for x in p)), v) for p in P]
 
 
+def test_forest_cross_validation_is_seeded_and_bounded():
+    X, T, _, _ = _table(260, 9, 11)
+    boot_for = lambda n: wl.bootstrap_indices(n, 4)  # noqa: E731
+    a = cart.cross_validate_forest(X[:200], T[:200], boot_for, None, 2, "logratio", 0, folds=4)
+    b = cart.cross_validate_forest(X[:200], T[:200], boot_for, None, 2, "logratio", 0, folds=4)
+    assert a == b and 0 < a <= 1
+    forest = cart.fit_forest(X[:200], T[:200], boot_for(200), None, 2, "logratio", 0)
+    st = forest.stats()
+    assert st["trees"] == 4 and st["leaves"] == sum(t.stats()["leaves"] for t in forest.trees)
+    # every leaf lists at most FOREST_KEEP variants, cheapest first, and `rest` is no smaller than the last listed cost
+    for tree in forest.to_nested():
+        stack = [tree]
+        while stack:
+            n = stack.pop()
+            if "leaf" in n:
+                assert 1 <= len(n["ids"]) <= cart.FOREST_KEEP and n["costs"] == sorted(n["costs"]) and n["rest"] >= n["costs"][-1]
+                assert len(set(n["ids"])) == len(n["ids"]) and n["costs"][0] >= 0
+            else:
+                stack += [n["left"], n["right"]]
+    # a forest's training-set prediction is never worse than guessing the globally best single variant
+    base = int(np.argmin(np.sum(np.log(T[:200]), axis=0)))
+    assert cart.geomean_ratio(T[:200], forest.predict(X[:200]), 0) >= cart.geomean_ratio(T[:200], np.full(200, base), 0)
+
+
 def test_shipped_selector_matches_the_stored_model():
     # the header compiled into the library must be the one generated from results/model.json
     from paper_1806_07060_amd import binding as mdg
