@@ -11,7 +11,8 @@ dataset (Section 5.2 of the paper):
   geomean             geometric mean of the same ratio (the figure this build is judged on)
   DTTR                mean of  f_model / f_default  (model against the traditional default dispatch)
   max speed-up        largest f_model / f_default
-and the cost of the tree traversal next to the kernel times (Section 5.3).
+and the cost of evaluating the model next to the kernel times (Section 5.3), both for a fresh shape and for a
+shape the per-thread memo in front of the model has seen.
 Writes results/selector_eval.json.
 """
 import json

@@ -5,14 +5,17 @@
 Reads the dataset written by the tuning run, takes the first 80 % of its
 (already shuffled) rows as the training set X and the rest as the held-out set
 Y (Section 3, 'Datasets'), trains one tree per (H, L) pair of Section 5 for
-both leaf rules and prints the table of model statistics the paper reports
+every leaf rule and prints the table of model statistics the paper reports
 (accuracy, DTPR, leaves, height) on Y.  Further synthetic tables (--extra: the
-go2 and po2 grids of Section 4.1, the wide sweep) are added to X only -- a
+go2 and po2 grids of Section 4.1, wider sweeps, grids and sweeps over the thin
+and flat corners) are added to X only -- a
 hybrid of several generation rules, as Section 3 allows -- after dropping any
 input whose (M, N, K) occurs in the square, skinny or convolution-lowered
 evaluation sets, which stay unseen.  The model that is compiled into the
 library is chosen by 5-fold cross-validation inside X -- the paper picks the
 best DTPR on the test set itself, which leaks; Y is only used for reporting.
+A forest of bagged trees with the chosen hyper-parameters (--forest-trees) is
+cross-validated the same way and replaces the single tree if it scores higher.
 Then writes csrc/mdg_select_generated.h and results/model.json.  Rebuild the
 library afterwards.
 """
