@@ -48,6 +48,10 @@
 extern "C" {
 #endif
 
+/* Largest M, N or K accepted (larger values are an invalid argument).  The kernels index rows, columns and k with
+   32-bit integers and add at most a tile or a K slice to a dimension: the limit keeps those sums below 2^31. */
+#define MDG_MAX_DIM 2147418111 /* 2^31 - 1 - 65536 */
+
 typedef enum { MDG_ROW_MAJOR = 101, MDG_COL_MAJOR = 102 } mdg_layout;
 typedef enum { MDG_NO_TRANS = 111, MDG_TRANS = 112, MDG_CONJ_TRANS = 113 /* same as MDG_TRANS for real data */ } mdg_op;
 

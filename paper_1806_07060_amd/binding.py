@@ -21,6 +21,8 @@ ERR_WORKSPACE, ERR_ILLEGAL_VARIANT, ERR_LAUNCH, ERR_BAD_VARIANT, ERR_NULL = -101
 FAMILY_DIRECT, FAMILY_TILED, FAMILY_SKINNY = 0, 1, 2
 FAMILY_NAMES = {0: "direct", 1: "tiled", 2: "skinny"}
 
+MAX_DIM = 2 ** 31 - 1 - 65536  # MDG_MAX_DIM
+
 # every symbol include/mdg_sgemm.h declares
 EXPORTS = ("mdg_sgemm", "mdg_sgemm_variant", "mdg_select", "mdg_select_default", "mdg_selector_name",
            "mdg_variant_count", "mdg_variant_info", "mdg_variant_legal", "mdg_workspace_bytes", "mdg_set_workspace",

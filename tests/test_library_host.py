@@ -80,6 +80,10 @@ def test_argument_validation_reports_first_bad_argument():
     assert call(N=-2) == -5
     assert call(K=-3) == -6
     assert call(M=2 ** 31) == -4
+    # the documented limit: the kernels add a tile or a K slice to a dimension in 32-bit arithmetic
+    assert call(M=mdg.MAX_DIM + 1, lda=mdg.MAX_DIM + 1, ldc=mdg.MAX_DIM + 1) == -4
+    assert call(N=mdg.MAX_DIM + 1) == -5 and call(K=mdg.MAX_DIM + 1, ldb=mdg.MAX_DIM + 1) == -6
+    assert mdg.MAX_DIM == 2 ** 31 - 1 - 65536
     assert call(A=0) == -8
     assert call(lda=3) == -9
     assert call(B=0) == -10
@@ -101,8 +105,9 @@ def test_legality_rules():
     vs = mdg.variants()
     n = len(vs)
     # variant 0 is legal for anything (soundness): odd sizes, unaligned pointers, huge N
-    for M, N, K in ((1, 1, 1), (7, 3, 1), (8191, 5, 13), (1, 2 ** 31 - 1, 1), (2 ** 31 - 1, 1, 1)):
+    for M, N, K in ((1, 1, 1), (7, 3, 1), (8191, 5, 13), (1, mdg.MAX_DIM, 1), (mdg.MAX_DIM, 1, 1)):
         assert mdg.mdg_variant_legal(0, 1, 0, M, N, K, K, K, M, 4, 4, 4) == 1
+    assert mdg.mdg_variant_legal(0, 1, 0, mdg.MAX_DIM + 1, 1, 1, 1, 1, mdg.MAX_DIM + 1, 4, 4, 4) == 0
     assert mdg.mdg_variant_legal(n, 0, 0, 1, 1, 1, 1, 1, 1) == mdg.ERR_BAD_VARIANT
     mdg.mdg_set_workspace(0, 0)
     for v in vs:
