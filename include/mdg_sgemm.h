@@ -61,7 +61,8 @@ enum {
   MDG_ERR_ILLEGAL_VARIANT = -102, /* forced variant cannot run on this input */
   MDG_ERR_LAUNCH = -103,          /* the HIP runtime rejected a launch or an event call */
   MDG_ERR_BAD_VARIANT = -104,     /* variant id out of range */
-  MDG_ERR_NULL = -105             /* a required output pointer is NULL */
+  MDG_ERR_NULL = -105,            /* a required output pointer is NULL */
+  MDG_ERR_ALIGNMENT = -106        /* a workspace pointer is not 256-byte aligned */
 };
 
 /* Kernel families (Section 2.3: one generic kernel plus one specialised kernel; the vector-shaped
@@ -121,7 +122,7 @@ int mdg_select(int transA, int transB, int64_t M, int64_t N, int64_t K);
 /*
  * What mdg_sgemm itself asks: the same model behind a memo of the shapes this thread asked about recently
  * (1024 entries in 512 two-way sets, thread-local).  Returns exactly what mdg_select returns; a repeated shape costs a
- * few nanoseconds instead of a model evaluation (Section 5.3 discusses the overhead of the model at run time).
+ * few nanoseconds instead of a model evaluation (the end of Section 5.4 discusses the overhead of the model at run time).
  */
 int mdg_select_memo(int transA, int transB, int64_t M, int64_t N, int64_t K);
 
@@ -152,8 +153,12 @@ size_t mdg_workspace_bytes(int variant, int64_t M, int64_t N, int64_t K);
 /*
  * Registers a caller-owned device buffer used by split-K variants for partial
  * sums.  The library keeps the pointer until it is replaced (NULL, 0 clears
- * it) and never frees it.  Calls that use the workspace must not overlap on
- * different streams.  Process-wide.
+ * it) and never frees it.  dev_ptr must be 256-byte aligned (MDG_ERR_ALIGNMENT
+ * otherwise).  Calls that use the workspace must not overlap on different
+ * streams.  Process-wide; may be called from any thread (a call that runs at
+ * the same time sees either the old or the new registration, never a mix),
+ * but replacing the workspace while GEMM calls that use it are still being
+ * issued or executed is the caller's race.
  */
 int mdg_set_workspace(void* dev_ptr, size_t bytes);
 
@@ -182,7 +187,7 @@ int mdg_time_calls(int variant, int transA, int transB, int64_t M, int64_t N, in
 
 /*
  * Host nanoseconds per call of mdg_select averaged over `iters` passes through
- * the n given problems (Section 5.3 reports the tree-traversal overhead).
+ * the n given problems (the end of Section 5.4 reports the tree-traversal overhead).
  */
 double mdg_time_select_ns(const int32_t* transA, const int32_t* transB, const int64_t* M, const int64_t* N,
                           const int64_t* K, int64_t n, int iters);

@@ -16,7 +16,7 @@ ROW_MAJOR, COL_MAJOR = 101, 102
 NO_TRANS, TRANS, CONJ_TRANS = 111, 112, 113
 
 OK = 0
-ERR_WORKSPACE, ERR_ILLEGAL_VARIANT, ERR_LAUNCH, ERR_BAD_VARIANT, ERR_NULL = -101, -102, -103, -104, -105
+ERR_WORKSPACE, ERR_ILLEGAL_VARIANT, ERR_LAUNCH, ERR_BAD_VARIANT, ERR_NULL, ERR_ALIGNMENT = -101, -102, -103, -104, -105, -106
 
 FAMILY_DIRECT, FAMILY_TILED, FAMILY_SKINNY = 0, 1, 2
 FAMILY_NAMES = {0: "direct", 1: "tiled", 2: "skinny"}

@@ -1,223 +1,15 @@
-// C-ABI entry points: validation, canonicalisation to the column-major problem,
-// variant table, legality, selection (generated decision tree), dispatch, and
-// the event-timing core of the tuning run.  Host code only; the kernels live in
+// C-ABI entry points that enqueue GPU work: the GEMM call, the forced-variant call and the event-timing core of
+// the tuning run.  Validation, selection and legality are host code in mdg_dispatch.cpp; the kernels live in
 // mdg_direct.hip, mdg_tiled.hip and mdg_skinny.hip.
-#include <chrono>
-#include <cstdio>
-#include <cstring>
-
 #include "mdg_internal.h"
-#include "mdg_variant_list.h"
-
-// Generated by paper_1806_07060_amd/tuning/codegen.py from the trained tree
-// (Section 3, 'Model and code generation'): defines mdg_generated_select() and
-// MDG_GENERATED_SELECTOR_NAME.
-#include "mdg_select_generated.h"
 
 namespace mdg {
 
-// ---- variant table ---------------------------------------------------------------------------
-
-struct DirectCfg { int tm, tn, lds; };
-struct TiledCfg { int bm, bn, bk, wgm, wgn, wgk; };
-struct SkinnyCfg { int nb, matrix; };
-
-static const DirectCfg kDirect[] = {
-#define X(c, TM, TN, L) {TM, TN, L},
-    MDG_DIRECT_CONFIGS(X)
-#undef X
-};
-static const TiledCfg kTiled[] = {
-#define X(c, BM, BN, BK, WGM, WGN, WGK) {BM, BN, BK, WGM, WGN, WGK},
-    MDG_TILED_CONFIGS(X)
-#undef X
-};
-static const SkinnyCfg kSkinny[] = {
-#define X(c, NB, MATRIX) {NB, MATRIX},
-    MDG_SKINNY_CONFIGS(X)
-#undef X
-};
-
-enum { FAM_DIRECT = MDG_FAMILY_DIRECT, FAM_TILED = MDG_FAMILY_TILED, FAM_SKINNY = MDG_FAMILY_SKINNY };
-
-struct RawVariant { int family, cfg, split_k; };
-static const RawVariant kRaw[] = {
-#define V(F, C, S) {FAM_##F, C, S},
-    MDG_VARIANTS(V)
-#undef V
-};
-constexpr int kVariantCount = (int)(sizeof(kRaw) / sizeof(kRaw[0]));
-
-static VariantEntry g_table[kVariantCount];
-static bool g_table_ready = false;
-
-static void build_table() {
-  for (int i = 0; i < kVariantCount; ++i) {
-    VariantEntry& e = g_table[i];
-    std::memset(&e, 0, sizeof(e));
-    mdg_variant_desc& d = e.desc;
-    const RawVariant& r = kRaw[i];
-    e.cfg = r.cfg;
-    d.id = i;
-    d.family = r.family;
-    d.split_k = r.split_k;
-    if (r.family == FAM_DIRECT) {
-      const DirectCfg& c = kDirect[r.cfg];
-      d.tile_m = 16 * c.tm, d.tile_n = 16 * c.tn, d.tile_k = c.lds ? 16 : 1, d.threads = 256;
-      d.sub_m = c.tm, d.sub_n = c.tn, d.vec = 1, d.lds = c.lds;
-      std::snprintf(d.name, sizeof(d.name), "direct_%dx%d_t%dx%d_%s", d.tile_m, d.tile_n, c.tm, c.tn,
-                    c.lds ? "lds" : "reg");
-    } else if (r.family == FAM_TILED) {
-      const TiledCfg& c = kTiled[r.cfg];
-      d.tile_m = c.bm, d.tile_n = c.bn, d.tile_k = c.bk, d.threads = 64 * c.wgm * c.wgn * c.wgk;
-      d.sub_m = c.bm / c.wgm, d.sub_n = c.bn / c.wgn, d.vec = 4, d.lds = 1;
-      if (c.wgk == 1)
-        std::snprintf(d.name, sizeof(d.name), "tiled_%dx%dx%d_w%dx%d_sk%d", c.bm, c.bn, c.bk, c.wgm, c.wgn, r.split_k);
-      else  // third wave count = wave groups that split each K step inside the work-group
-        std::snprintf(d.name, sizeof(d.name), "tiled_%dx%dx%d_w%dx%dx%d_sk%d", c.bm, c.bn, c.bk, c.wgm, c.wgn, c.wgk,
-                      r.split_k);
-    } else {
-      const SkinnyCfg& c = kSkinny[r.cfg];
-      d.tile_m = 256, d.tile_n = c.nb, d.tile_k = 8, d.threads = 256;
-      d.sub_m = 1, d.sub_n = c.nb, d.vec = 1, d.lds = 0;
-      if (c.matrix) {  // matrix-core member: a strip of 64 rows (16 when A is transposed), K cut over the waves
-        d.tile_m = 64, d.tile_k = 4, d.threads = c.nb == 16 ? 1024 : 512, d.sub_m = 16, d.vec = 4, d.lds = 1;
-        std::snprintf(d.name, sizeof(d.name), "skinny_mfma_nb%d_sk%d", c.nb, r.split_k);
-      } else {
-        std::snprintf(d.name, sizeof(d.name), "skinny_nb%d_sk%d", c.nb, r.split_k);
-      }
-    }
-  }
-  // Fallback links (tried in turn when a variant is not legal for an input):
-  //   tiled with split_k > 1 -> the same tile with the next smaller split (split 1 is legal everywhere)
-  //   skinny                 -> the next wider skinny kernel with the same split (the usual reason is
-  //                             too many columns); past the widest, the narrowest kernel at least as
-  //                             wide with the next smaller split; past those, the tiled 32x32 tile
-  //   everything else        -> variant 0
-  for (int i = 0; i < kVariantCount; ++i) {
-    const RawVariant& r = kRaw[i];
-    int fb = 0;
-    if (r.family == FAM_TILED && r.split_k > 1) {
-      int best_split = 0;
-      for (int j = 0; j < kVariantCount; ++j)
-        if (kRaw[j].family == FAM_TILED && kRaw[j].cfg == r.cfg && kRaw[j].split_k < r.split_k &&
-            kRaw[j].split_k > best_split)
-          best_split = kRaw[j].split_k, fb = j;
-    } else if (r.family == FAM_SKINNY) {
-      const int nb = kSkinny[r.cfg].nb;
-      int j = -1;
-      for (int k = 0; k < kVariantCount; ++k)  // wider, same split: the narrowest such
-        if (kRaw[k].family == FAM_SKINNY && kRaw[k].split_k == r.split_k && kSkinny[kRaw[k].cfg].nb > nb &&
-            (j < 0 || kSkinny[kRaw[k].cfg].nb < kSkinny[kRaw[j].cfg].nb))
-          j = k;
-      if (j < 0)
-        for (int k = 0; k < kVariantCount; ++k) {  // at least as wide, the largest smaller split, narrowest first
-          if (kRaw[k].family != FAM_SKINNY || kRaw[k].split_k >= r.split_k || kSkinny[kRaw[k].cfg].nb < nb) continue;
-          if (j < 0 || kRaw[k].split_k > kRaw[j].split_k ||
-              (kRaw[k].split_k == kRaw[j].split_k && kSkinny[kRaw[k].cfg].nb < kSkinny[kRaw[j].cfg].nb))
-            j = k;
-        }
-      if (j < 0)
-        for (int k = 0; k < kVariantCount && j < 0; ++k)
-          if (kRaw[k].family == FAM_TILED && kRaw[k].split_k == 1 && kTiled[kRaw[k].cfg].bm == 32 &&
-              kTiled[kRaw[k].cfg].bn == 32)
-            j = k;
-      fb = j < 0 ? 0 : j;
-    }
-    g_table[i].desc.fallback = fb;
-  }
-  g_table_ready = true;
-}
-
-const VariantEntry* variant_table(int* count) {
-  if (!g_table_ready) build_table();
-  if (count) *count = kVariantCount;
-  return g_table;
-}
-
-// ---- workspace --------------------------------------------------------------------------------
-
-static float* g_ws = nullptr;
-static size_t g_ws_bytes = 0;
-
-static size_t workspace_need(const VariantEntry& e, int64_t M, int64_t N) {
-  return e.desc.split_k > 1 ? (size_t)e.desc.split_k * (size_t)M * (size_t)N * sizeof(float) : 0;
-}
-
-// ---- validation ------------------------------------------------------------------------------
-
-static inline bool is_trans(int t) { return t == MDG_TRANS || t == MDG_CONJ_TRANS; }
-static inline int64_t max1(int64_t v) { return v > 1 ? v : 1; }
-
-// Checks the public argument list; on success fills the column-major problem.
-// Row-major is mapped through C^T = op(B)^T op(A)^T: a row-major matrix is the
-// column-major storage of its transpose, so the operands swap and keep their flags.
-static int canonicalise(int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
-                        const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
-                        void* stream, GemmArgs* out) {
-  if (layout != MDG_ROW_MAJOR && layout != MDG_COL_MAJOR) return -1;
-  if (transA != MDG_NO_TRANS && !is_trans(transA)) return -2;
-  if (transB != MDG_NO_TRANS && !is_trans(transB)) return -3;
-  if (M < 0 || M > MDG_MAX_DIM) return -4;
-  if (N < 0 || N > MDG_MAX_DIM) return -5;
-  if (K < 0 || K > MDG_MAX_DIM) return -6;
-  const bool tA = is_trans(transA), tB = is_trans(transB);
-  const bool col = layout == MDG_COL_MAJOR;
-  // extent of the contiguous index of each stored matrix
-  const int64_t a_min = col ? (tA ? K : M) : (tA ? M : K);
-  const int64_t b_min = col ? (tB ? N : K) : (tB ? K : N);
-  const int64_t c_min = col ? M : N;
-  const bool reads_ab = (M > 0 && N > 0 && K > 0 && alpha != 0.f);
-  if (reads_ab && A == nullptr) return -8;
-  if (lda < max1(a_min)) return -9;
-  if (reads_ab && B == nullptr) return -10;
-  if (ldb < max1(b_min)) return -11;
-  if (M > 0 && N > 0 && C == nullptr) return -13;
-  if (ldc < max1(c_min)) return -14;
-  GemmArgs g;
-  if (col) {
-    g.tA = tA, g.tB = tB, g.M = M, g.N = N, g.A = A, g.B = B, g.lda = lda, g.ldb = ldb;
-  } else {
-    g.tA = tB, g.tB = tA, g.M = N, g.N = M, g.A = B, g.B = A, g.lda = ldb, g.ldb = lda;
-  }
-  g.K = K, g.alpha = alpha, g.beta = beta, g.C = C, g.ldc = ldc;
-  g.ws = g_ws, g.ws_bytes = g_ws_bytes;
-  g.stream = (hipStream_t)stream;
-  *out = g;
-  return MDG_OK;
-}
-
-// ---- legality (Section 4.1: a class must be a valid configuration for the input) -----------------
-
-static bool legal(const VariantEntry& e, const GemmArgs& g) {
-  const mdg_variant_desc& d = e.desc;
-  if (workspace_need(e, g.M, g.N) > g.ws_bytes) return false;
-  if (d.split_k > 1) {
-    // every slice must own at least one K step, otherwise the variant duplicates a smaller split
-    const int64_t step = d.family == FAM_TILED ? d.tile_k : 1;
-    if ((g.K + step - 1) / step < d.split_k) return false;
-  }
-  switch (d.family) {
-    case FAM_DIRECT: {
-      const int64_t tiles = ((g.M + d.tile_m - 1) / d.tile_m) * ((g.N + d.tile_n - 1) / d.tile_n);
-      return tiles <= 0x7fffffffLL;
-    }
-    case FAM_TILED: {
-      const int64_t tiles = ((g.M + d.tile_m - 1) / d.tile_m) * ((g.N + d.tile_n - 1) / d.tile_n) * d.split_k;
-      return tiles <= 0x7fffffffLL;
-    }
-    case FAM_SKINNY:
-      // streams A once per group of sub_n columns: only sensible (and allowed) for a few groups
-      return (g.N + d.sub_n - 1) / d.sub_n <= 4;
-  }
-  return false;
-}
-
 static int run_variant(const VariantEntry& e, const GemmArgs& g) {
   switch (e.desc.family) {
-    case FAM_DIRECT: return launch_direct(e.cfg, g);
-    case FAM_TILED: return launch_tiled(e.cfg, e.desc.split_k, g);
-    case FAM_SKINNY: return launch_skinny(e.cfg, e.desc.split_k, g);
+    case MDG_FAMILY_DIRECT: return launch_direct(e.cfg, g);
+    case MDG_FAMILY_TILED: return launch_tiled(e.cfg, e.desc.split_k, g);
+    case MDG_FAMILY_SKINNY: return launch_skinny(e.cfg, e.desc.split_k, g);
   }
   return MDG_ERR_BAD_VARIANT;
 }
@@ -235,60 +27,10 @@ static inline bool handled_without_gemm(const GemmArgs& g, int* status) {
   return false;
 }
 
-static inline int clamp_variant(int v) { return (v < 0 || v >= kVariantCount) ? 0 : v; }
-
-// The compiled model behind a memo of recent shapes.  Callers repeat shapes (the layers of a network, the steps
-// of a solver), and a forest of trees costs a few hundred nanoseconds to evaluate -- most of it instruction-cache
-// misses in megabytes of generated branches -- against a few nanoseconds for a hit here.  512 sets of two entries
-// (most recently used first), one table per thread (no locking, no sharing); the model is a pure function, so a
-// hit returns exactly what the model would.
-struct SelectMemoEntry {
-  int64_t M, N, K;
-  int32_t key;  // tA | tB << 1 | 4 (0 = empty)
-  int32_t variant;
-};
-static thread_local SelectMemoEntry g_select_memo[512][2];
-
-static inline int memo_select(int tA, int tB, int64_t M, int64_t N, int64_t K) {
-  const uint64_t h = (uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^
-                     (uint64_t)K * 0x165667B19E3779F9ull ^ (uint64_t)(tA | (tB << 1)) * 0xD6E8FEB86659FD93ull;
-  SelectMemoEntry* set = g_select_memo[h >> 55];
-  const int32_t key = (tA ? 1 : 0) | (tB ? 2 : 0) | 4;
-  if (set[0].key == key && set[0].M == M && set[0].N == N && set[0].K == K) return set[0].variant;
-  if (set[1].key == key && set[1].M == M && set[1].N == N && set[1].K == K) {
-    const SelectMemoEntry hit = set[1];
-    set[1] = set[0], set[0] = hit;
-    return hit.variant;
-  }
-  const int v = mdg_generated_select(tA, tB, M, N, K);
-  set[1] = set[0];
-  set[0].M = M, set[0].N = N, set[0].K = K, set[0].key = key, set[0].variant = v;
-  return v;
-}
-
-enum SelectorKind { SEL_TREE = 0, SEL_DEFAULT = 1 };
-
-static int default_select(int tA, int tB, int64_t M, int64_t N, int64_t K);
-
 static int dispatch(const GemmArgs& g, SelectorKind sel) {
   int st;
   if (handled_without_gemm(g, &st)) return st;
-  int n;
-  const VariantEntry* tab = variant_table(&n);
-  int v = sel == SEL_TREE ? memo_select(g.tA, g.tB, g.M, g.N, g.K) : default_select(g.tA, g.tB, g.M, g.N, g.K);
-  v = clamp_variant(v);
-  for (int hops = 0; hops < n && v != 0 && !legal(tab[v], g); ++hops) v = tab[v].desc.fallback;
-  if (!legal(tab[v], g)) v = 0;
-  return run_variant(tab[v], g);
-}
-
-// Traditional dispatch (Section 5, "default"): one tiled configuration, tuned
-// on a 1024-cube, and one direct configuration, tuned on a 256-cube, switched by
-// a threshold on the problem size.  The two ids and the threshold are written by
-// the tuning run into the generated header.
-static int default_select(int, int, int64_t M, int64_t N, int64_t K) {
-  const double work = (double)M * (double)N * (double)K;
-  return work >= MDG_GENERATED_DEFAULT_THRESHOLD ? MDG_GENERATED_DEFAULT_TILED : MDG_GENERATED_DEFAULT_DIRECT;
+  return run_variant(variant_table(nullptr)[choose_variant(g, sel)], g);
 }
 
 }  // namespace mdg
@@ -300,7 +42,10 @@ extern "C" {
 int mdg_sgemm(int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha, const float* A,
               int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc, void* stream) {
   GemmArgs g;
-  int st = canonicalise(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, &g);
+  float* ws;
+  size_t ws_bytes;
+  registered_workspace(&ws, &ws_bytes);
+  int st = canonicalise(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, ws, ws_bytes, &g);
   if (st != MDG_OK) return st;
   return dispatch(g, SEL_TREE);
 }
@@ -308,9 +53,12 @@ int mdg_sgemm(int layout, int transA, int transB, int64_t M, int64_t N, int64_t 
 int mdg_sgemm_variant(int variant, int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
                       const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
                       void* stream) {
-  if (variant < 0 || variant >= kVariantCount) return MDG_ERR_BAD_VARIANT;
+  if (variant < 0 || variant >= variant_count()) return MDG_ERR_BAD_VARIANT;
   GemmArgs g;
-  int st = canonicalise(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, &g);
+  float* ws;
+  size_t ws_bytes;
+  registered_workspace(&ws, &ws_bytes);
+  int st = canonicalise(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, ws, ws_bytes, &g);
   if (st != MDG_OK) return st;
   if (handled_without_gemm(g, &st)) return st;
   const VariantEntry& e = variant_table(nullptr)[variant];
@@ -319,89 +67,18 @@ int mdg_sgemm_variant(int variant, int layout, int transA, int transB, int64_t M
   return run_variant(e, g);
 }
 
-int mdg_select(int transA, int transB, int64_t M, int64_t N, int64_t K) {
-  return clamp_variant(mdg_generated_select(transA != 0, transB != 0, M, N, K));
-}
-
-int mdg_select_memo(int transA, int transB, int64_t M, int64_t N, int64_t K) {
-  return clamp_variant(memo_select(transA != 0, transB != 0, M, N, K));
-}
-
-int mdg_select_default(int transA, int transB, int64_t M, int64_t N, int64_t K) {
-  return clamp_variant(default_select(transA != 0, transB != 0, M, N, K));
-}
-
-const char* mdg_selector_name(void) { return MDG_GENERATED_SELECTOR_NAME; }
-
-int mdg_variant_count(void) { return kVariantCount; }
-
-int mdg_variant_info(int variant, mdg_variant_desc* out) {
-  if (variant < 0 || variant >= kVariantCount) return MDG_ERR_BAD_VARIANT;
-  if (!out) return MDG_ERR_NULL;
-  *out = variant_table(nullptr)[variant].desc;
-  return MDG_OK;
-}
-
-int mdg_variant_legal(int variant, int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
-                      int64_t ldc, const void* A, const void* B, const void* C) {
-  if (variant < 0 || variant >= kVariantCount) return MDG_ERR_BAD_VARIANT;
-  if (M < 0 || N < 0 || K < 0 || M > MDG_MAX_DIM || N > MDG_MAX_DIM || K > MDG_MAX_DIM) return 0;
-  GemmArgs g;
-  g.tA = transA != 0, g.tB = transB != 0, g.M = M, g.N = N, g.K = K, g.alpha = 1.f, g.beta = 0.f;
-  g.A = (const float*)A, g.B = (const float*)B, g.C = (float*)const_cast<void*>(C);
-  g.lda = lda, g.ldb = ldb, g.ldc = ldc, g.ws = g_ws, g.ws_bytes = g_ws_bytes, g.stream = nullptr;
-  return legal(variant_table(nullptr)[variant], g) ? 1 : 0;
-}
-
-size_t mdg_workspace_bytes(int variant, int64_t M, int64_t N, int64_t K) {
-  (void)K;
-  if (variant < 0 || variant >= kVariantCount || M < 0 || N < 0) return 0;
-  return workspace_need(variant_table(nullptr)[variant], M, N);
-}
-
-int mdg_set_workspace(void* dev_ptr, size_t bytes) {
-  if (dev_ptr == nullptr || bytes == 0) {
-    g_ws = nullptr, g_ws_bytes = 0;
-    return MDG_OK;
-  }
-  if (reinterpret_cast<uintptr_t>(dev_ptr) & 255) return -1;  // must be 256-byte aligned
-  g_ws = (float*)dev_ptr, g_ws_bytes = bytes;
-  return MDG_OK;
-}
-
-const char* mdg_status_string(int status) {
-  switch (status) {
-    case MDG_OK: return "ok";
-    case -1: return "invalid layout (argument 1)";
-    case -2: return "invalid transA (argument 2)";
-    case -3: return "invalid transB (argument 3)";
-    case -4: return "invalid M (argument 4)";
-    case -5: return "invalid N (argument 5)";
-    case -6: return "invalid K (argument 6)";
-    case -8: return "A is NULL (argument 8)";
-    case -9: return "lda too small (argument 9)";
-    case -10: return "B is NULL (argument 10)";
-    case -11: return "ldb too small (argument 11)";
-    case -13: return "C is NULL (argument 13)";
-    case -14: return "ldc too small (argument 14)";
-    case MDG_ERR_WORKSPACE: return "registered workspace too small for this variant";
-    case MDG_ERR_ILLEGAL_VARIANT: return "variant is not legal for this input";
-    case MDG_ERR_LAUNCH: return "HIP launch or event call failed";
-    case MDG_ERR_BAD_VARIANT: return "variant id out of range";
-    case MDG_ERR_NULL: return "required output pointer is NULL";
-  }
-  return "unknown status";
-}
-
 int mdg_time_calls(int variant, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha, const float* A,
                    int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc, int n_sets,
                    int64_t a_set_stride, int64_t b_set_stride, int64_t c_set_stride, int warmup, int reps, int spans,
                    float* ms_per_call, void* stream) {
-  if (variant < -2 || variant >= kVariantCount) return MDG_ERR_BAD_VARIANT;
+  if (variant < -2 || variant >= variant_count()) return MDG_ERR_BAD_VARIANT;
   if (!ms_per_call || n_sets < 1 || reps < 1 || spans < 1 || warmup < 0) return MDG_ERR_NULL;
   GemmArgs g0;
+  float* ws;
+  size_t ws_bytes;
+  registered_workspace(&ws, &ws_bytes);
   int st = canonicalise(MDG_COL_MAJOR, transA ? MDG_TRANS : MDG_NO_TRANS, transB ? MDG_TRANS : MDG_NO_TRANS, M, N, K,
-                        alpha, A, lda, B, ldb, beta, C, ldc, stream, &g0);
+                        alpha, A, lda, B, ldb, beta, C, ldc, stream, ws, ws_bytes, &g0);
   if (st != MDG_OK) return st;
   const VariantEntry* e = variant >= 0 ? &variant_table(nullptr)[variant] : nullptr;
   if (e) {
@@ -442,30 +119,6 @@ int mdg_time_calls(int variant, int transA, int transB, int64_t M, int64_t N, in
   (void)hipEventDestroy(ev0);
   (void)hipEventDestroy(ev1);
   return st;
-}
-
-static double time_select(bool memo, const int32_t* transA, const int32_t* transB, const int64_t* M, const int64_t* N,
-                          const int64_t* K, int64_t n, int iters) {
-  if (!transA || !transB || !M || !N || !K || n <= 0 || iters <= 0) return -1.0;
-  volatile int sink = 0;
-  auto t0 = std::chrono::steady_clock::now();
-  for (int it = 0; it < iters; ++it)
-    for (int64_t i = 0; i < n; ++i)
-      sink = sink + (memo ? memo_select(transA[i] != 0, transB[i] != 0, M[i], N[i], K[i])
-                          : mdg_generated_select(transA[i], transB[i], M[i], N[i], K[i]));
-  auto t1 = std::chrono::steady_clock::now();
-  (void)sink;
-  return std::chrono::duration<double, std::nano>(t1 - t0).count() / ((double)n * (double)iters);
-}
-
-double mdg_time_select_ns(const int32_t* transA, const int32_t* transB, const int64_t* M, const int64_t* N,
-                          const int64_t* K, int64_t n, int iters) {
-  return time_select(false, transA, transB, M, N, K, n, iters);
-}
-
-double mdg_time_select_memo_ns(const int32_t* transA, const int32_t* transB, const int64_t* M, const int64_t* N,
-                               const int64_t* K, int64_t n, int iters) {
-  return time_select(true, transA, transB, M, N, K, n, iters);
 }
 
 }  // extern "C"

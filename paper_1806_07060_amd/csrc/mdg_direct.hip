@@ -146,11 +146,11 @@ static int launch_cfg(const GemmArgs& g) {
   dim3 grid((unsigned)(tiles_m * tiles_n));
   dim3 block(256);
   if (g.tA) {
-    if (g.tB) direct_kernel<TM, TN, LDS, true, true><<<grid, block, 0, g.stream>>>(p);
-    else direct_kernel<TM, TN, LDS, true, false><<<grid, block, 0, g.stream>>>(p);
+    if (g.tB) direct_kernel<TM, TN, LDS, true, true><<<grid, block, 0, stream_of(g)>>>(p);
+    else direct_kernel<TM, TN, LDS, true, false><<<grid, block, 0, stream_of(g)>>>(p);
   } else {
-    if (g.tB) direct_kernel<TM, TN, LDS, false, true><<<grid, block, 0, g.stream>>>(p);
-    else direct_kernel<TM, TN, LDS, false, false><<<grid, block, 0, g.stream>>>(p);
+    if (g.tB) direct_kernel<TM, TN, LDS, false, true><<<grid, block, 0, stream_of(g)>>>(p);
+    else direct_kernel<TM, TN, LDS, false, false><<<grid, block, 0, stream_of(g)>>>(p);
   }
   return check_launch();
 }
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void scale_c_kernel(float* C, int64_t ldc, int
 int launch_scale_c(const GemmArgs& g) {
   if (g.beta == 1.f) return MDG_OK;
   int64_t total = g.M * g.N;
-  scale_c_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, g.stream>>>(g.C, g.ldc, (int)g.M, (int)g.N,
+  scale_c_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream_of(g)>>>(g.C, g.ldc, (int)g.M, (int)g.N,
                                                                                    g.beta);
   return check_launch();
 }
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* ws, flo
 
 int launch_splitk_reduce(int split_k, const GemmArgs& g) {
   int64_t total = g.M * g.N;
-  splitk_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, g.stream>>>(
+  splitk_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream_of(g)>>>(
       g.ws, g.C, g.ldc, (int)g.M, (int)g.N, split_k, g.alpha, g.beta);
   return check_launch();
 }

@@ -1,28 +1,13 @@
-// Internal declarations shared by the translation units of libmdg_sgemm.so.
+// Internal declarations shared by the GPU translation units of libmdg_sgemm.so.
 // Everything here is about the column-major problem the C ABI has already
 // canonicalised to (Eq. 1, Section 2.2 of the paper).
 #pragma once
 
 #include <hip/hip_runtime.h>
-#include <stddef.h>
-#include <stdint.h>
 
-#include "../../include/mdg_sgemm.h"
+#include "mdg_host.h"
 
 namespace mdg {
-
-struct GemmArgs {
-  int tA, tB;  // 0 / 1, column-major problem
-  int64_t M, N, K;
-  float alpha, beta;
-  const float* A;
-  const float* B;
-  float* C;
-  int64_t lda, ldb, ldc;
-  float* ws;        // registered workspace (may be null)
-  size_t ws_bytes;  // its size
-  hipStream_t stream;
-};
 
 // Per-family launchers.  `cfg` is the index inside the family's configuration list
 // (mdg_variant_list.h), `split_k` the number of K slices.  Return MDG_OK or MDG_ERR_LAUNCH.
@@ -36,12 +21,7 @@ int launch_scale_c(const GemmArgs& g);
 // C = alpha * sum_s ws[s] + beta * C ; ws holds split_k tight column-major M x N slices.
 int launch_splitk_reduce(int split_k, const GemmArgs& g);
 
-struct VariantEntry {
-  mdg_variant_desc desc;
-  int cfg;  // index in the family's list
-};
-
-const VariantEntry* variant_table(int* count);
+inline hipStream_t stream_of(const GemmArgs& g) { return static_cast<hipStream_t>(g.stream); }
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? MDG_OK : MDG_ERR_LAUNCH; }
 

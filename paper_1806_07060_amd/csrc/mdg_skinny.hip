@@ -383,8 +383,8 @@ static int launch_mfma_cfg(int split_k, const GemmArgs& g) {
   const dim3 grid((unsigned)strips, (unsigned)split_k, (unsigned)col_groups), block(64 * (NBK == 1 ? 16 : 8));
 #define MDG_THIN(TA, TB)                                                                        \
   do {                                                                                          \
-    if (vec) thin_mfma_kernel<TA, TB, NBK, true><<<grid, block, 0, g.stream>>>(p);              \
-    else thin_mfma_kernel<TA, TB, NBK, false><<<grid, block, 0, g.stream>>>(p);                 \
+    if (vec) thin_mfma_kernel<TA, TB, NBK, true><<<grid, block, 0, stream_of(g)>>>(p);              \
+    else thin_mfma_kernel<TA, TB, NBK, false><<<grid, block, 0, stream_of(g)>>>(p);                 \
   } while (0)
   if (g.tA) {
     if (g.tB) MDG_THIN(true, true);
@@ -413,12 +413,12 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
   if (!g.tA) {
     constexpr int W = NB <= 4 ? 16 : 4;
     dim3 grid((unsigned)((g.M + 63) / 64), (unsigned)split_k, (unsigned)col_groups);
-    if (g.tB) skinny_n_kernel<NB, true><<<grid, dim3(64 * W), 0, g.stream>>>(p);
-    else skinny_n_kernel<NB, false><<<grid, dim3(64 * W), 0, g.stream>>>(p);
+    if (g.tB) skinny_n_kernel<NB, true><<<grid, dim3(64 * W), 0, stream_of(g)>>>(p);
+    else skinny_n_kernel<NB, false><<<grid, dim3(64 * W), 0, stream_of(g)>>>(p);
   } else {
     dim3 grid((unsigned)((g.M + 15) / 16), (unsigned)split_k, (unsigned)col_groups);
-    if (g.tB) skinny_t_kernel<NB, true><<<grid, dim3(256), 0, g.stream>>>(p);
-    else skinny_t_kernel<NB, false><<<grid, dim3(256), 0, g.stream>>>(p);
+    if (g.tB) skinny_t_kernel<NB, true><<<grid, dim3(256), 0, stream_of(g)>>>(p);
+    else skinny_t_kernel<NB, false><<<grid, dim3(256), 0, stream_of(g)>>>(p);
   }
   int st = check_launch();
   if (st != MDG_OK || split_k == 1) return st;

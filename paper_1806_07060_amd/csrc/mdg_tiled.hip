@@ -515,11 +515,11 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
   p.b_vec = ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
   dim3 grid((unsigned)(tiles_m * tiles_n * split_k)), block(64 * WGM * WGN * WGK);
   if (g.tA) {
-    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, true><<<grid, block, 0, g.stream>>>(p);
-    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, false><<<grid, block, 0, g.stream>>>(p);
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, true><<<grid, block, 0, stream_of(g)>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, false><<<grid, block, 0, stream_of(g)>>>(p);
   } else {
-    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, true><<<grid, block, 0, g.stream>>>(p);
-    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, false><<<grid, block, 0, g.stream>>>(p);
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, true><<<grid, block, 0, stream_of(g)>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, false><<<grid, block, 0, stream_of(g)>>>(p);
   }
   int st = check_launch();
   if (st != MDG_OK || split_k == 1) return st;

@@ -11,7 +11,7 @@ dataset (Section 5.2 of the paper):
   geomean             geometric mean of the same ratio (the figure this build is judged on)
   DTTR                mean of  f_model / f_default  (model against the traditional default dispatch)
   max speed-up        largest f_model / f_default
-and the cost of evaluating the model next to the kernel times (Section 5.3), both for a fresh shape and for a
+and the cost of evaluating the model next to the kernel times (end of Section 5.4), both for a fresh shape and for a
 shape the per-thread memo in front of the model has seen.
 Writes results/selector_eval.json.
 """
@@ -75,7 +75,7 @@ def main():
     out["heldout_geomean_pct"] = 100.0 * held["geomean"]
     out["heldout_dtpr"] = held["dtpr"]
 
-    # selector overhead (Section 5.3): host nanoseconds per traversal vs the time of the selected kernel
+    # selector overhead (end of Section 5.4): host nanoseconds per traversal vs the time of the selected kernel
     Xte, Tte = tab4["X"][te], tab4["T"][te]
     ns = mdg.mdg_time_select_ns(Xte[:, 3], Xte[:, 4], Xte[:, 0], Xte[:, 1], Xte[:, 2], iters=2000)
     pred = predict_with_library(Xte)

@@ -79,3 +79,22 @@ def legal_variants(case):
         tA, tB, M, N, lda, ldb = c.tB(), c.tA(), c.N, c.M, c.ldb, c.lda
     return [v for v in range(mdg.mdg_variant_count())
             if mdg.mdg_variant_legal(v, tA, tB, M, N, c.K, lda, ldb, c.ldc) == 1]
+
+
+def run_case_many(case, variants, poison=False):
+    """One upload of the case's operands, then one call per entry of `variants` (None = mdg_sgemm, i.e. the
+    selector; an id = that variant forced), each on a fresh copy of C0.  Returns (A, B, C0, [(status, C_host)])."""
+    torch = torch_mod()
+    c = case.resolved()
+    A, B, C0 = wl.make_operands(c, poison=poison)
+    dA, dB, dC0 = (torch.from_numpy(x).cuda() for x in (A, B, C0))
+    stream = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for v in variants:
+        dC = dC0.clone()
+        args = (c.layout, c.transA, c.transB, c.M, c.N, c.K, c.alpha, dA.data_ptr(), c.lda, dB.data_ptr(), c.ldb,
+                c.beta, dC.data_ptr(), c.ldc, stream)
+        st = mdg.mdg_sgemm(*args) if v is None else mdg.mdg_sgemm_variant(v, *args)
+        torch.cuda.synchronize()
+        outs.append((st, dC.cpu().numpy()))
+    return A, B, C0, outs

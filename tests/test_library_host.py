@@ -160,3 +160,45 @@ def test_the_memo_in_front_of_the_model_returns_what_the_model_returns():
             assert mdg.mdg_select_memo(tA, tB, 777, 33, 2049) == mdg.mdg_select(tA, tB, 777, 33, 2049)
     X = shapes[:64]
     assert mdg.mdg_time_select_ns(X[:, 3], X[:, 4], X[:, 0], X[:, 1], X[:, 2], iters=3, memo=True) > 0
+
+
+def test_first_calls_from_many_threads_agree():
+    # the variant table is built on first use: concurrent first calls from several threads must all see the
+    # finished table (a fresh process, so that no earlier test has built it already)
+    import subprocess
+    import sys
+    code = r'''
+import sys, threading
+sys.path.insert(0, %r)
+from paper_1806_07060_amd import binding as mdg
+L = mdg.lib()
+n = 16
+out = [None] * n
+go = threading.Barrier(n)
+def work(i):
+    go.wait()
+    rows = []
+    for v in range(mdg.mdg_variant_count()):
+        d = mdg.mdg_variant_info(v)
+        rows.append((d["name"], d["fallback"], d["split_k"], mdg.mdg_variant_legal(v, 0, 0, 300, 40, 5000, 300, 5000, 300)))
+    rows.append(mdg.mdg_select(i & 1, 0, 100 + i, 200, 300))
+    out[i] = rows
+ts = [threading.Thread(target=work, args=(i,)) for i in range(n)]
+[t.start() for t in ts]
+[t.join() for t in ts]
+assert all(o is not None and o[:-1] == out[0][:-1] for o in out)
+assert all(0 <= f < len(out[0]) - 1 for _, f, _, _ in out[0][:-1])
+print("ok")
+''' % ROOT
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", r.stderr
+
+
+def test_workspace_registration_errors_have_their_own_code():
+    assert mdg.mdg_set_workspace(4096 + 4, 1 << 20) == mdg.ERR_ALIGNMENT
+    assert "aligned" in mdg.mdg_status_string(mdg.ERR_ALIGNMENT)
+    assert mdg.mdg_set_workspace(4096, 1 << 20) == 0  # host code only stores the pair; nothing is dereferenced
+    sk = next(d["id"] for d in mdg.variants() if d["split_k"] == 4 and d["family"] == mdg.FAMILY_TILED)
+    assert mdg.mdg_variant_legal(sk, 0, 0, 128, 128, 4096, 128, 4096, 128) == 1
+    assert mdg.mdg_set_workspace(0, 0) == 0
+    assert mdg.mdg_variant_legal(sk, 0, 0, 128, 128, 4096, 128, 4096, 128) == 0
