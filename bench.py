@@ -19,6 +19,12 @@ in HBM before the timed region.  Prints ONE JSON line.
                of its launches (HIP events on the launch stream, inside the timed steps) vs the MI355X
                fp32 matrix peak
   cpu_baseline the CPU oracle timed on a bounded sample of the same workload (reported, not a target)
+  selector_measured   (extra leg, bounded) on a seeded sample of the held-out random-sweep shapes plus the 24
+               squares: every legal variant timed with the tuning protocol, and mdg_sgemm itself (selector,
+               legality, kernel) timed the same way; pct_exhaustive_best_measured = geomean of t_best / t_mdg_sgemm,
+               and the same with the measured cost of a fresh-shape model evaluation added to t_mdg_sgemm
+  per_config   (extra leg, bounded) geomean TFLOP/s and roofline fraction of mdg_sgemm on samples of the skinny and
+               convolution-lowered workloads; empty_launch_us = the smallest call that launches a kernel
 """
 import argparse
 import json
@@ -43,7 +49,9 @@ def geomean(xs):
 def kernel_symbol(desc, tA, tB):
     """Name of the GPU kernel a variant launches for these transposes (matches the rocprofv3 kernel trace)."""
     b = lambda x: "true" if x else "false"
-    if desc["family"] == 1:
+    if desc["family"] == 3:  # indirect: the tiled kernel on packed operands (A as stored untransposed, B transposed)
+        tA, tB = 0, 1
+    if desc["family"] in (1, 3):
         wgm, wgn = desc["tile_m"] // desc["sub_m"], desc["tile_n"] // desc["sub_n"]
         wgk = desc["threads"] // (64 * wgm * wgn)
         return f"tiled_kernel<{desc['tile_m']}, {desc['tile_n']}, {desc['tile_k']}, {wgm}, {wgn}, {wgk}, {b(tA)}, {b(tB)}>"
@@ -76,12 +84,79 @@ def cpu_baseline(sample_n=4096):
                       f"({secs:.1f} s wall on {go.max_threads()} threads)"}
 
 
+def extra_legs(torch, mdg, wl, sptr, heldout_sample=64, skinny_sample=24, conv_sample=15):
+    """The bounded side measurements: selector quality measured end to end, secondary workloads, launch floor."""
+    import numpy as np
+    from paper_1806_07060_amd.tuning import harness
+    variants = mdg.variants()
+    pools = harness.Pools(torch, harness.POOL_BYTES // 4)
+    out = {}
+
+    def sgemm_seconds(c, span_ms=1.0, spans=3):
+        n_sets, sa, sb, sc = pools.layout(c)
+        t = harness.time_variant(-1, c, pools, n_sets, sa, sb, sc, sptr, 1, 1, 1)
+        reps = int(min(200, max(3, math.ceil(span_ms * 1e-3 / max(t, 1e-7)))))
+        return harness.time_variant(-1, c, pools, n_sets, sa, sb, sc, sptr, 1, reps, spans)
+
+    # -- selector, measured: exhaustive search over the variant table against what mdg_sgemm does by itself
+    _, held = wl.split_train_heldout(wl.config4())
+    pick = np.random.Generator(np.random.PCG64(wl.case_seed(41, 0))).choice(len(held), heldout_sample, replace=False)
+    sample = [held[i].resolved() for i in sorted(pick.tolist())] + [c.resolved() for c in wl.config1()]
+    fresh = wl.fresh_shapes(50000, 2)
+    select_ns = mdg.mdg_time_select_ns(fresh[:, 3], fresh[:, 4], fresh[:, 0], fresh[:, 1], fresh[:, 2], iters=2)
+    rows = []
+    for c in sample:
+        times = harness.measure_case(c, pools, sptr, variants)
+        t_sel = sgemm_seconds(c)
+        rows.append((c, float(np.min(times)), t_sel, int(np.argmin(times))))
+    r = np.array([tb / ts for _, tb, ts, _ in rows])
+    rc = np.array([tb / (ts + select_ns * 1e-9) for _, tb, ts, _ in rows])
+    nh = heldout_sample
+    gm = lambda x: float(np.exp(np.mean(np.log(np.minimum(x, 1.0)))))  # noqa: E731  (a ratio above 1 is timing noise)
+    out["selector_measured"] = {
+        "n": len(rows), "n_heldout": nh, "n_square": len(rows) - nh,
+        "pct_exhaustive_best_measured": 100.0 * gm(r),
+        "pct_exhaustive_best_measured_heldout": 100.0 * gm(r[:nh]),
+        "pct_exhaustive_best_measured_square": 100.0 * gm(r[nh:]),
+        "pct_exhaustive_best_measured_with_selector_cost": 100.0 * gm(rc),
+        "pct_exhaustive_best_measured_with_selector_cost_heldout": 100.0 * gm(rc[:nh]),
+        "fresh_shape_selector_ns": float(select_ns),
+        "worst": [{"case": c.name, "shape": [c.M, c.N, c.K, c.tA(), c.tB()], "ratio": float(tb / ts),
+                   "best": variants[b]["name"]} for c, tb, ts, b in sorted(rows, key=lambda x: x[1] / x[2])[:3]],
+        "protocol": "every legal variant and mdg_sgemm timed by the library's event core on rotating operand sets: "
+                    "probe call, then the median of 3 spans of about 1 ms",
+    }
+
+    # -- secondary workloads through mdg_sgemm (bounded samples)
+    per_config = {}
+    for key, every, n_pick, stream_id in (("skinny_fc", wl.config2(), skinny_sample, 1), ("conv_lowered", wl.config3(), conv_sample, 2)):
+        pick = np.random.Generator(np.random.PCG64(wl.case_seed(41, stream_id))).choice(len(every), n_pick, replace=False)
+        tf, fr, gbs = [], [], []
+        for i in sorted(pick.tolist()):
+            c = every[i].resolved()
+            t = sgemm_seconds(c)
+            tf.append(c.flops() / t / 1e12)
+            fr.append(max(c.flops() / (FP32_MATRIX_PEAK_TFLOPS * 1e12), c.algorithmic_bytes() / (HBM_PEAK_GBS * 1e9)) / t)
+            gbs.append(c.algorithmic_bytes() / t / 1e9)
+        per_config[key] = {"n": n_pick, "of": len(every), "geomean_tflops": geomean(tf), "geomean_roofline_frac": geomean(fr),
+                           "best_gb_per_s": max(gbs)}
+    out["per_config"] = per_config
+
+    # -- launch floor: K = 0 on a 1 x 1 C is one tiny scaling kernel and nothing else
+    tiny = wl.GemmCase(1, 1, 0, beta=0.5).resolved()
+    n_sets, sa, sb, sc = pools.layout(tiny)
+    out["empty_launch_us"] = 1e6 * harness.time_variant(-1, tiny, pools, n_sets, sa, sb, sc, sptr, 20, 500, 5)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing (profiling runs)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the bounded side legs (measured selector quality, secondary workloads, launch floor)")
     ap.add_argument("--sizes", type=str, default="256,512,1024,2048,4096,8192")
     ap.add_argument("--workload", choices=("square", "skinny", "conv"), default="square",
                     help="square = the headline sweep (default); skinny = the fully-connected-like shapes "
@@ -256,7 +331,9 @@ def main():
                    "selector": mdg.mdg_selector_name()},
         "aggregate_tflops": float(sum(c.flops() for c in cases) * args.steps / total_s / 1e12),
         "pct_fp32_peak_large": float(100.0 * geomean(large) / FP32_MATRIX_PEAK_TFLOPS) if large else None,
-        "pct_exhaustive_best_heldout": (sel_eval or {}).get("heldout_geomean_pct"),
+        "pct_exhaustive_best_heldout_stored_table": (sel_eval or {}).get("heldout_geomean_pct"),
+        "pct_exhaustive_best_heldout_stored_table_with_selector_cost":
+            (sel_eval or {}).get("heldout_geomean_with_selector_cost_pct"),
         "per_shape": [{"case": c.name, "variant": variants[v]["name"], "ms": float(m), "tflops": float(t),
                        "ms_single_call_events": float(e),
                        "roofline_frac": float(max(c.flops() / (FP32_MATRIX_PEAK_TFLOPS * 1e12),
@@ -265,6 +342,10 @@ def main():
                       for c, v, m, t, e in zip(cases, chosen, b2b_ms, tflops, med_ms)],
         "roofline": roofline,
     }
+    if not args.no_extras and args.workload == "square":
+        del dev  # the side legs bring their own operand pools
+        torch.cuda.empty_cache()
+        out.update(extra_legs(torch, mdg, wl, sptr))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     mdg.mdg_set_workspace(0, 0)

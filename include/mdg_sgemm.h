@@ -70,7 +70,10 @@ enum {
 typedef enum {
   MDG_FAMILY_DIRECT = 0, /* register-blocked, bounds-checked, vector ALUs; any shape */
   MDG_FAMILY_TILED = 1,  /* LDS-staged, double-buffered, fp32 matrix-core (MFMA) tiles */
-  MDG_FAMILY_SKINNY = 2  /* N <= a few columns: streams A once, bandwidth-bound */
+  MDG_FAMILY_SKINNY = 2, /* N <= a few columns: streams A once, bandwidth-bound */
+  MDG_FAMILY_INDIRECT = 3 /* Section 2.3's indirect path: pad / transpose helper passes copy op(A), op(B) into the
+                             workspace in the tiled kernel's preferred layout, then the tiled kernel runs on the
+                             copies with every tile whole; the variant's time includes the helpers */
 } mdg_family;
 
 /* One point of the tuning space (Section 2.3 lists the kind of parameters: work-group tile, per-thread
@@ -147,12 +150,14 @@ int mdg_variant_info(int variant, mdg_variant_desc* out);
 int mdg_variant_legal(int variant, int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
                       int64_t ldc, const void* A, const void* B, const void* C);
 
-/* Bytes of workspace `variant` needs for a problem of this size (0 for most variants). */
+/* Bytes of workspace `variant` needs for a problem of this size (0 for most variants): split_k slices of the
+   M x N result for split-K variants; for indirect variants the padded operand copies, taken over the transpose
+   combination that needs most. */
 size_t mdg_workspace_bytes(int variant, int64_t M, int64_t N, int64_t K);
 
 /*
  * Registers a caller-owned device buffer used by split-K variants for partial
- * sums.  The library keeps the pointer until it is replaced (NULL, 0 clears
+ * sums and by indirect variants for their packed operand copies.  The library keeps the pointer until it is replaced (NULL, 0 clears
  * it) and never frees it.  dev_ptr must be 256-byte aligned (MDG_ERR_ALIGNMENT
  * otherwise).  Calls that use the workspace must not overlap on different
  * streams.  Process-wide; may be called from any thread (a call that runs at

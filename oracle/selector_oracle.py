@@ -18,6 +18,9 @@ Section 4.2; metrics of Section 5.2), step by step and in the paper's notation:
   forest           several such trees, each grown on a bootstrap sample whose row indices are an
                    input; leaves list the mean integer cost of their cheapest variants and the
                    forest predicts the variant with the smallest summed cost (see 'forest' below)
+  gated model      the single tree for inputs whose work M*N*K is below a gate, the forest for the
+                   others; the gate maximises the ratio metric with each model's evaluation time
+                   charged to its predictions (cost-effectiveness, Section 3 requirement 2)
   accuracy         right predictions / test instances
   DTPR             mean over the test inputs of f_pred(s) / f_best(s)
 
@@ -291,6 +294,38 @@ def forest_scores(trees, x, n_variants):
 def predict_forest(trees, x, n_variants):
     total = forest_scores(trees, x, n_variants)
     return total.index(min(total))  # first minimum = lowest id
+
+
+# ----- the selector's own cost ---------------------------------------------------------------
+# Section 3, requirement 2 (cost-effectiveness): the time to select a-bar counts against it,
+# f_a-bar(i) + c_a-bar < f_a(i).  A forest costs an order of magnitude more to evaluate than one tree, so a
+# gated model lets the tree answer the inputs whose work M*N*K is below a gate and the forest the others.
+
+def predict_gated(tree, trees, gate, x, n_variants):
+    """x = expanded feature tuple (x[6] = M*N*K): the single tree below the gate, the forest at or above it."""
+    return predict(tree, x) if x[6] < gate else predict_forest(trees, x, n_variants)
+
+
+def ratio_with_selector_cost(times_row, v, cost_seconds, fallback=0):
+    """t_best / (t_v + c): the performance ratio when the model that predicted v took cost_seconds to evaluate."""
+    return times_row[best_variant(times_row)] / (effective_time(times_row, v, fallback) + cost_seconds)
+
+
+def choose_gate(X, times, pred_tree, pred_forest, tree_ns, forest_ns, gate_set, fallback=0):
+    """The gate of gate_set (first maximum in its order) with the highest geometric mean of the cost-inclusive
+    ratio, given each model's prediction for every row of X (expanded feature tuples)."""
+    best, best_score = None, -math.inf
+    for G in gate_set:
+        logs = []
+        for x, row, pt, pf in zip(X, times, pred_tree, pred_forest):
+            if x[6] < G:
+                logs.append(math.log(ratio_with_selector_cost(row, pt, tree_ns * 1e-9, fallback)))
+            else:
+                logs.append(math.log(ratio_with_selector_cost(row, pf, forest_ns * 1e-9, fallback)))
+        score = math.exp(math.fsum(logs) / len(logs))
+        if score > best_score:
+            best, best_score = G, score
+    return best, best_score
 
 
 def tree_stats(tree):

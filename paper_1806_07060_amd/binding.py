@@ -18,8 +18,8 @@ NO_TRANS, TRANS, CONJ_TRANS = 111, 112, 113
 OK = 0
 ERR_WORKSPACE, ERR_ILLEGAL_VARIANT, ERR_LAUNCH, ERR_BAD_VARIANT, ERR_NULL, ERR_ALIGNMENT = -101, -102, -103, -104, -105, -106
 
-FAMILY_DIRECT, FAMILY_TILED, FAMILY_SKINNY = 0, 1, 2
-FAMILY_NAMES = {0: "direct", 1: "tiled", 2: "skinny"}
+FAMILY_DIRECT, FAMILY_TILED, FAMILY_SKINNY, FAMILY_INDIRECT = 0, 1, 2, 3
+FAMILY_NAMES = {0: "direct", 1: "tiled", 2: "skinny", 3: "indirect"}
 
 MAX_DIM = 2 ** 31 - 1 - 65536  # MDG_MAX_DIM
 

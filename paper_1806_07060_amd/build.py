@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmdg_sgemm.so")
-SOURCES = ["mdg_dispatch.cpp", "mdg_api.hip", "mdg_direct.hip", "mdg_tiled.hip", "mdg_skinny.hip"]  # .cpp = host only
+SOURCES = ["mdg_dispatch.cpp", "mdg_api.hip", "mdg_direct.hip", "mdg_tiled.hip", "mdg_skinny.hip", "mdg_indirect.hip"]  # .cpp = host only
 # packed fp32 instructions are switched off on purpose (see the flag), everything else is plain -O3
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -10,6 +10,7 @@ static int run_variant(const VariantEntry& e, const GemmArgs& g) {
     case MDG_FAMILY_DIRECT: return launch_direct(e.cfg, g);
     case MDG_FAMILY_TILED: return launch_tiled(e.cfg, e.desc.split_k, g);
     case MDG_FAMILY_SKINNY: return launch_skinny(e.cfg, e.desc.split_k, g);
+    case MDG_FAMILY_INDIRECT: return launch_indirect(e.cfg, e.desc.tile_m, e.desc.tile_n, e.desc.tile_k, g);
   }
   return MDG_ERR_BAD_VARIANT;
 }
@@ -62,7 +63,7 @@ int mdg_sgemm_variant(int variant, int layout, int transA, int transB, int64_t M
   if (st != MDG_OK) return st;
   if (handled_without_gemm(g, &st)) return st;
   const VariantEntry& e = variant_table(nullptr)[variant];
-  if (workspace_need(e, g.M, g.N) > g.ws_bytes) return MDG_ERR_WORKSPACE;
+  if (workspace_need(e, g.tA, g.tB, g.M, g.N, g.K) > g.ws_bytes) return MDG_ERR_WORKSPACE;
   if (!legal(e, g)) return MDG_ERR_ILLEGAL_VARIANT;
   return run_variant(e, g);
 }
@@ -82,7 +83,7 @@ int mdg_time_calls(int variant, int transA, int transB, int64_t M, int64_t N, in
   if (st != MDG_OK) return st;
   const VariantEntry* e = variant >= 0 ? &variant_table(nullptr)[variant] : nullptr;
   if (e) {
-    if (workspace_need(*e, g0.M, g0.N) > g0.ws_bytes) return MDG_ERR_WORKSPACE;
+    if (workspace_need(*e, g0.tA, g0.tB, g0.M, g0.N, g0.K) > g0.ws_bytes) return MDG_ERR_WORKSPACE;
     if (!legal(*e, g0)) return MDG_ERR_ILLEGAL_VARIANT;
   }
   hipStream_t s = (hipStream_t)stream;

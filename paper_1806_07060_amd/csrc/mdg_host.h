@@ -34,8 +34,18 @@ struct VariantEntry {
 const VariantEntry* variant_table(int* count);
 int variant_count();
 
-// Bytes of split-K workspace variant e needs for an M x N result (0 when it does not split K).
-size_t workspace_need(const VariantEntry& e, int64_t M, int64_t N);
+// What the indirect path (Section 2.3: pad / transpose helpers, then the tiled kernel) does to a problem: padded
+// extents, which operands need a packed copy, and the floats of workspace those copies take.
+struct IndirectPlan {
+  int64_t Mp, Np, Kp;
+  bool pack_a, pack_b;
+  size_t a_floats, b_floats;
+};
+IndirectPlan plan_indirect(int tile_m, int tile_n, int tile_k, int tA, int tB, int64_t M, int64_t N, int64_t K);
+
+// Bytes of workspace variant e needs for this problem: split-K slices of the M x N result, or the packed
+// operand copies of an indirect variant (0 for everything else).
+size_t workspace_need(const VariantEntry& e, int tA, int tB, int64_t M, int64_t N, int64_t K);
 
 // The workspace registered with mdg_set_workspace, read as one consistent (pointer, size) pair.
 void registered_workspace(float** ws, size_t* bytes);

@@ -12,7 +12,12 @@ namespace mdg {
 // Per-family launchers.  `cfg` is the index inside the family's configuration list
 // (mdg_variant_list.h), `split_k` the number of K slices.  Return MDG_OK or MDG_ERR_LAUNCH.
 int launch_direct(int cfg, const GemmArgs& g);
-int launch_tiled(int cfg, int split_k, const GemmArgs& g);
+// a_rows / b_cols: rows of op(A) / columns of op(B) that exist in memory when that is more than M / N (padded
+// copies made by the indirect path); the kernel may then load whole tiles past M / N.  0 = M / N.
+int launch_tiled(int cfg, int split_k, const GemmArgs& g, int64_t a_rows = 0, int64_t b_cols = 0);
+// Indirect path: pad / transpose helper passes into g.ws, then tiled configuration `tiled_cfg` (its tile sizes
+// are passed along) on the packed operands.
+int launch_indirect(int tiled_cfg, int tile_m, int tile_n, int tile_k, const GemmArgs& g);
 int launch_skinny(int cfg, int split_k, const GemmArgs& g);
 
 // C = beta * C (beta == 0 writes zeros without reading C).

@@ -27,8 +27,12 @@
 // non-contracted index contiguous).  Global loads are float4 along whichever
 // index is contiguous in memory (also for operands that are only 4-byte
 // aligned); operands stored with k contiguous are transposed on their way into
-// LDS (four 4-byte writes; the +4 padding spreads them over the banks).  One barrier per K step; global loads run two K steps
-// ahead (two register sets), LDS stages alternate.
+// LDS: the four lanes of a quad hold four neighbouring rows, exchange their
+// 4 x 4 block with two rounds of cross-lane moves, and each lane then writes one
+// 16-byte vector along the LDS row (with the +4 padding the sixteen rows a
+// group of lanes writes fall on distinct banks: no bank conflicts).  One barrier
+// per K step; global loads run two K steps ahead (two register sets), LDS stages
+// alternate.
 #include <type_traits>
 
 #include "mdg_internal.h"
@@ -81,11 +85,37 @@ struct TiledParams {
   float* ws;
   int64_t lda, ldb, ldc;
   int M, N, K;
+  int Ma, Nb;  // rows of op(A) / columns of op(B) that may be loaded: M and N, or more when the operands are padded copies
   int tiles_m, tiles_n;
   int split_k, k_per_split;
   float alpha, beta;
   int a_vec, b_vec;  // 1 if float4 global loads of that operand are aligned
 };
+
+// Value of `x` in the lane whose index within its quad differs in bit 0 (xor1) / bit 1 (xor2).
+__device__ __forceinline__ float quad_xor1(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_xor2(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true));
+}
+// 4 x 4 transpose across the four lanes of a quad: lane t enters with row t (elements 0..3) and leaves with
+// column t.  Two rounds that each swap one index bit between "lane" and "element"; b0 / b1 = bit 0 / 1 of the
+// lane's index in its quad.  All lanes of the quad must be active.
+__device__ __forceinline__ void quad_transpose(floatx4& r, bool b0, bool b1) {
+  {
+    const float s0 = b0 ? r[0] : r[1], s1 = b0 ? r[2] : r[3];
+    const float g0 = quad_xor1(s0), g1 = quad_xor1(s1);
+    r[0] = b0 ? g0 : r[0], r[1] = b0 ? r[1] : g0;
+    r[2] = b0 ? g1 : r[2], r[3] = b0 ? r[3] : g1;
+  }
+  {
+    const float s0 = b1 ? r[0] : r[2], s1 = b1 ? r[1] : r[3];
+    const float g0 = quad_xor2(s0), g1 = quad_xor2(s1);
+    r[0] = b1 ? g0 : r[0], r[2] = b1 ? r[2] : g0;
+    r[1] = b1 ? g1 : r[1], r[3] = b1 ? r[3] : g1;
+  }
+}
 
 constexpr int kPad = 4;
 constexpr int kGroupM = 8;  // tiles per group along M in the tile ordering
@@ -101,15 +131,16 @@ struct OperandLoader {
 
   // Slot -> (non-contracted index, k) of the first of its four elements.
   //   MN-major: consecutive lanes run along mn (one k row per BMN/4 lanes).
-  //   K-major : a wave covers 16 mn x 16 k (four lanes per 64-byte row piece), further waves /
-  //             slots step through the other 16-wide k chunks and mn ranges.  With the +4 row
-  //             padding the four transposing LDS stores of such a wave fall on distinct banks.
+  //   K-major : a wave covers 16 mn x 16 k: the four lanes of a quad take four neighbouring mn rows (so
+  //             that they can transpose their 4 x 4 block among themselves before the LDS store), the
+  //             quads step through the four 16-byte pieces of a 64-byte row piece, then through the mn
+  //             rows; further waves / slots take the other 16-wide k chunks and mn ranges.
   __device__ __forceinline__ static void coords(int slot, int tid, int& mn, int& k) {
     int v = tid + slot * NT;
     if (KMAJOR) {
-      const int l = v & 63, chunk = v >> 6;
-      k = (chunk % (BK / 16)) * 16 + (l & 3) * 4;
-      mn = (chunk / (BK / 16)) * 16 + (l >> 2);
+      const int l = v & 63, chunk = v >> 6, q = l >> 2;
+      k = (chunk % (BK / 16)) * 16 + (q & 3) * 4;
+      mn = (chunk / (BK / 16)) * 16 + (q >> 2) * 4 + (l & 3);
     } else {
       mn = (v % (BMN / 4)) * 4;
       k = v / (BMN / 4);
@@ -200,8 +231,12 @@ struct OperandLoader {
       int mn, k;
       coords(s, tid, mn, k);
       if (KMAJOR) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) S[(k + e) * LD + mn] = r[s][e];
+        // lane t of the quad holds X(mn - t + 0..3 -> its own row mn, k .. k+3); after the transpose it holds
+        // k + t of the quad's four rows: one 16-byte store along the LDS row k + t
+        const int t = tid & 3;
+        floatx4 c = r[s];
+        quad_transpose(c, (t & 1) != 0, (t & 2) != 0);
+        *reinterpret_cast<floatx4*>(&S[(k + t) * LD + (mn - t)]) = c;
       } else {
         *reinterpret_cast<floatx4*>(&S[k * LD + mn]) = r[s];
       }
@@ -280,7 +315,7 @@ void tiled_kernel(TiledParams p) {
   const int k_end = min(p.K, k_begin + p.k_per_split);
   const int n_steps = (k_end - k_begin + BK - 1) / BK;
 
-  const bool a_full = (m0 + BM <= p.M), b_full = (n0 + BN <= p.N);  // tile inside the operand along m / n
+  const bool a_full = (m0 + BM <= p.Ma), b_full = (n0 + BN <= p.Nb);  // tile inside the operand along m / n
   const bool a_al = p.a_vec != 0, b_al = p.b_vec != 0;              // 16-byte loads of that operand are aligned
 
   floatx16 acc[FN][FM];
@@ -305,8 +340,8 @@ void tiled_kernel(TiledParams p) {
     if (ti < n_steps) {
       const int k0 = k_begin + ti * BK;
       const bool kfull = (k0 + BK <= k_end);
-      LoadA::load(qa, p.A, p.lda, m0, k0, p.M, k_end, a_full && kfull, a_al, tid);
-      LoadB::load(qb, p.B, p.ldb, n0, k0, p.N, k_end, b_full && kfull, b_al, tid);
+      LoadA::load(qa, p.A, p.lda, m0, k0, p.Ma, k_end, a_full && kfull, a_al, tid);
+      LoadB::load(qb, p.B, p.ldb, n0, k0, p.Nb, k_end, b_full && kfull, b_al, tid);
     }
   };
 
@@ -499,11 +534,12 @@ void tiled_kernel(TiledParams p) {
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int WGK>
-static int launch_cfg(int split_k, const GemmArgs& g) {
+static int launch_cfg(int split_k, const GemmArgs& g, int64_t a_rows, int64_t b_cols) {
   TiledParams p;
   p.A = g.A, p.B = g.B, p.C = g.C, p.ws = g.ws;
   p.lda = g.lda, p.ldb = g.ldb, p.ldc = g.ldc;
   p.M = (int)g.M, p.N = (int)g.N, p.K = (int)g.K;
+  p.Ma = (int)(a_rows > g.M ? a_rows : g.M), p.Nb = (int)(b_cols > g.N ? b_cols : g.N);
   const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   if (tiles_m * tiles_n * split_k > 0x7fffffffLL) return MDG_ERR_LAUNCH;
   p.tiles_m = (int)tiles_m, p.tiles_n = (int)tiles_n;
@@ -526,11 +562,11 @@ static int launch_cfg(int split_k, const GemmArgs& g) {
   return launch_splitk_reduce(split_k, g);
 }
 
-int launch_tiled(int cfg, int split_k, const GemmArgs& g) {
+int launch_tiled(int cfg, int split_k, const GemmArgs& g, int64_t a_rows, int64_t b_cols) {
   switch (cfg) {
 #define X(c, BM, BN, BK, WGM, WGN, WGK) \
   case c:                               \
-    return launch_cfg<BM, BN, BK, WGM, WGN, WGK>(split_k, g);
+    return launch_cfg<BM, BN, BK, WGM, WGN, WGK>(split_k, g, a_rows, b_cols);
     MDG_TILED_CONFIGS(X)
 #undef X
   }

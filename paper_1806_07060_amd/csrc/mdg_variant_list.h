@@ -55,6 +55,15 @@
   X(4, 16, 1)                 \
   X(5, 32, 1)
 
+// Indirect path (Section 2.3): helper passes write padded, untransposed copies of the operands into the
+// workspace, then the tiled configuration TILED_CFG runs on them with every tile interior.
+//   X(cfg, TILED_CFG)
+#define MDG_INDIRECT_CONFIGS(X) \
+  X(0, 4)                       \
+  X(1, 2)                       \
+  X(2, 0)                       \
+  X(3, 8)
+
 // The variants: (family, cfg, split_k).  Order defines the public variant ids;
 // id 0 must be legal for every input (the universal fallback).
 //   V(family, cfg, split_k)
@@ -123,4 +132,8 @@
   V(SKINNY, 4, 1)       \
   V(SKINNY, 5, 1)       \
   V(SKINNY, 4, 4)       \
-  V(SKINNY, 5, 4)
+  V(SKINNY, 5, 4)  \
+  V(INDIRECT, 0, 1)     \
+  V(INDIRECT, 1, 1)     \
+  V(INDIRECT, 2, 1)     \
+  V(INDIRECT, 3, 1)

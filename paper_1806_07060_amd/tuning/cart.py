@@ -303,19 +303,25 @@ def sweep(X_train, T_train, X_test, T_test, leaf_rule="majority", fallback=0, H_
     return rows
 
 
-def cross_validate(X, T, H, L, leaf_rule, fallback=0, folds=5):
-    """Mean held-out log ratio over `folds` contiguous folds of the (already shuffled) training set."""
+def cross_predict(X, T, fit, folds=5):
+    """Out-of-fold predictions: `folds` contiguous folds of the (already shuffled) training set; every row is
+    predicted by the model `fit(X_train, T_train)` grown without its fold.  Returns one variant id per row."""
     X = np.asarray(X, dtype=np.int64)
     T = np.asarray(T, dtype=np.float64)
     n = X.shape[0]
     edges = np.linspace(0, n, folds + 1).astype(int)
-    logs = []
+    pred = np.empty(n, dtype=np.int64)
     for k in range(folds):
         test = np.arange(edges[k], edges[k + 1])
         train = np.concatenate([np.arange(0, edges[k]), np.arange(edges[k + 1], n)])
-        tree = fit_cart(X[train], T[train], H, L, leaf_rule, fallback)
-        logs.append(np.log(ratios(T[test], tree.predict(X[test]), fallback)))
-    return float(np.exp(np.mean(np.concatenate(logs))))
+        pred[test] = fit(X[train], T[train]).predict(X[test])
+    return pred
+
+
+def cross_validate(X, T, H, L, leaf_rule, fallback=0, folds=5):
+    """Geometric mean of the out-of-fold performance ratio (`folds` contiguous folds of the training set)."""
+    pred = cross_predict(X, T, lambda Xa, Ta: fit_cart(Xa, Ta, H, L, leaf_rule, fallback), folds)
+    return geomean_ratio(T, pred, fallback)
 
 
 def select_model(X_train, T_train, fallback=0, folds=5, H_set=H_SET, L_set=L_SET,
@@ -410,16 +416,51 @@ def fit_forest(X, times, bootstrap, H=None, L=4, leaf_rule="logratio", fallback=
     return Forest(trees, ids, costs, rest, T.shape[1])
 
 
+def cross_predict_forest(X, T, bootstrap_for, H, L, leaf_rule, fallback=0, folds=5):
+    """Out-of-fold predictions of a forest; `bootstrap_for(n)` returns the bootstrap index arrays for n training rows."""
+    return cross_predict(X, T, lambda Xa, Ta: fit_forest(Xa, Ta, bootstrap_for(Xa.shape[0]), H, L, leaf_rule, fallback), folds)
+
+
 def cross_validate_forest(X, T, bootstrap_for, H, L, leaf_rule, fallback=0, folds=5):
-    """As cross_validate, for a forest; `bootstrap_for(n)` returns the bootstrap index arrays for n training rows."""
-    X = np.asarray(X, dtype=np.int64)
-    T = np.asarray(T, dtype=np.float64)
-    n = X.shape[0]
-    edges = np.linspace(0, n, folds + 1).astype(int)
-    logs = []
-    for k in range(folds):
-        test = np.arange(edges[k], edges[k + 1])
-        train = np.concatenate([np.arange(0, edges[k]), np.arange(edges[k + 1], n)])
-        forest = fit_forest(X[train], T[train], bootstrap_for(train.size), H, L, leaf_rule, fallback)
-        logs.append(np.log(ratios(T[test], forest.predict(X[test]), fallback)))
-    return float(np.exp(np.mean(np.concatenate(logs))))
+    """As cross_validate, for a forest."""
+    return geomean_ratio(T, cross_predict_forest(X, T, bootstrap_for, H, L, leaf_rule, fallback, folds), fallback)
+
+
+# ---- cost of the selector itself (Section 3, requirement 2: the cost of selecting must be lower than the
+# improvement, f_a-bar(i) + c_a-bar < f_a(i)) --------------------------------------------------------------------
+# A forest predicts a little better than one tree and costs an order of magnitude more to evaluate; for a call
+# of a few microseconds that cost exceeds what the better prediction saves.  The gated model lets the single tree
+# answer inputs whose work M*N*K is below a gate G and the forest the others.  G is chosen on out-of-fold
+# predictions with every predicted time charged the evaluation cost of the model that made it.
+
+GATE_SET = (0,) + tuple(1 << e for e in range(20, 43)) + (INT64_MAX,)  # 0 = forest only, INT64_MAX = tree only
+
+
+def selector_cost_ratios(times, pred, cost_seconds, fallback=0):
+    """t_best / (t_pred + c) per row: the performance ratio with the selector's own cost charged to the model."""
+    T = np.asarray(times, dtype=np.float64)
+    E = effective_times(T, fallback)
+    rows = np.arange(T.shape[0])
+    return T.min(axis=1) / (E[rows, np.asarray(pred)] + np.asarray(cost_seconds, dtype=np.float64))
+
+
+def gated_predict(X, gate, pred_tree, pred_forest):
+    """Row-wise: the tree's prediction where M*N*K < gate, the forest's elsewhere."""
+    work = expand_features(X)[:, FEATURES.index("MNK")]
+    return np.where(work < int(gate), np.asarray(pred_tree), np.asarray(pred_forest)).astype(np.int64)
+
+
+def choose_gate(X, T, pred_tree, pred_forest, tree_ns, forest_ns, fallback=0, gate_set=GATE_SET):
+    """The gate with the highest cost-inclusive geomean ratio (first maximum in gate_set order), and the table
+    of all candidates.  pred_tree / pred_forest are out-of-fold predictions for the rows of X."""
+    work = expand_features(X)[:, FEATURES.index("MNK")]
+    table = []
+    for G in gate_set:
+        by_tree = work < int(G)
+        pred = np.where(by_tree, pred_tree, pred_forest)
+        cost = np.where(by_tree, tree_ns, forest_ns) * 1e-9
+        r = selector_cost_ratios(T, pred, cost, fallback)
+        table.append({"gate": int(G), "geomean_with_cost": float(np.exp(np.mean(np.log(r)))),
+                      "rows_by_tree": int(by_tree.sum())})
+    best = max(table, key=lambda r: r["geomean_with_cost"])
+    return best["gate"], table

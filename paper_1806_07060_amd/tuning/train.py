@@ -15,7 +15,13 @@ evaluation sets, which stay unseen.  The model that is compiled into the
 library is chosen by 5-fold cross-validation inside X -- the paper picks the
 best DTPR on the test set itself, which leaks; Y is only used for reporting.
 A forest of bagged trees with the chosen hyper-parameters (--forest-trees) is
-cross-validated the same way and replaces the single tree if it scores higher.
+cross-validated the same way.  What ships is the gated pair of both: the tree
+answers inputs whose work M*N*K is below a gate, the forest the others, and the
+gate is the one that maximises the out-of-fold ratio with the evaluation time of
+the answering model (--tree-ns, --forest-ns: measured host nanoseconds per
+evaluation) added to every predicted time -- Section 3, requirement 2: the cost
+of selecting must stay below the improvement.  Gate 0 ships the forest alone,
+an infinite gate the tree alone.
 Then writes csrc/mdg_select_generated.h and results/model.json.  Rebuild the
 library afterwards.
 """
@@ -56,10 +62,11 @@ def split(table, train_fraction=0.8):
 
 
 def training_union(tab4, extra_tables, exclude_tables, seed=180607060):
-    """X = first 80 % of the random sweep + the extra tables, minus shapes of the excluded tables; shuffled."""
-    tr, _ = split(tab4)
+    """X = first 80 % of the random sweep + the extra tables, minus shapes of the excluded tables and of the
+    held-out 20 % of the sweep; shuffled."""
+    tr, te = split(tab4)
     Xs, Ts, src = [tab4["X"][tr]], [tab4["T"][tr]], ["cfg4"] * tab4["X"][tr].shape[0]
-    banned = set()
+    banned = {tuple(r[:3]) for r in tab4["X"][te].tolist()}  # a held-out (M, N, K) may not come back through an extra table
     for t in exclude_tables:
         banned |= {tuple(r[:3]) for r in t["X"].tolist()}
     for name, t in extra_tables:
@@ -68,6 +75,8 @@ def training_union(tab4, extra_tables, exclude_tables, seed=180607060):
         Ts.append(t["T"][keep])
         src += [name] * int(keep.sum())
     X, T = np.vstack(Xs), np.vstack(Ts)
+    held = {tuple(r[:3]) for r in tab4["X"][te].tolist()}
+    assert not any(tuple(r[:3]) in held for x in Xs[1:] for r in x.tolist()), "held-out inputs leaked into the training set"
     perm = np.random.Generator(np.random.PCG64(seed)).permutation(X.shape[0])
     return X[perm], T[perm], [src[i] for i in perm]
 
@@ -109,6 +118,10 @@ def main(argv=None):
     ap.add_argument("--forest-trees", type=int, default=12,
                     help="also cross-validate a forest of this many bagged trees with the chosen (H, L, leaf rule) and "
                          "ship it instead of the single tree if it scores higher (0 = single tree only)")
+    ap.add_argument("--tree-ns", type=float, default=32.0,
+                    help="host nanoseconds per evaluation of the single tree (if-then-else), fresh shapes")
+    ap.add_argument("--forest-ns", type=float, default=490.0,
+                    help="host nanoseconds per evaluation of the forest (table walk), fresh shapes")
     ap.add_argument("--no-write", action="store_true")
     args = ap.parse_args(argv)
 
@@ -153,10 +166,15 @@ def main(argv=None):
 
     # forest of bagged trees with the same hyper-parameters: shipped only if cross-validation prefers it
     forest, forest_cv, forest_held = None, None, None
+    gate, gate_table = cart.INT64_MAX, None
     if args.forest_trees > 0:
         from .. import workloads as wl
         boot_for = lambda n: wl.bootstrap_indices(n, args.forest_trees)  # noqa: E731
-        forest_cv = cart.cross_validate_forest(Xtr, Ttr, boot_for, best["H"], best["L"], best["leaf_rule"], links, args.folds)
+        oof_forest = cart.cross_predict_forest(Xtr, Ttr, boot_for, best["H"], best["L"], best["leaf_rule"], links, args.folds)
+        forest_cv = cart.geomean_ratio(Ttr, oof_forest, links)
+        oof_tree = cart.cross_predict(Xtr, Ttr, lambda Xa, Ta: cart.fit_cart(Xa, Ta, best["H"], best["L"], best["leaf_rule"], links),
+                                      args.folds)
+        gate, gate_table = cart.choose_gate(Xtr, Ttr, oof_tree, oof_forest, args.tree_ns, args.forest_ns, links)
         cand = cart.fit_forest(Xtr, Ttr, boot_for(Xtr.shape[0]), best["H"], best["L"], best["leaf_rule"], links)
         fpred = cand.predict(Xte)
         forest_held = {"accuracy": cart.accuracy(fpred, cart.labels_from_table(Tte)), "dtpr": cart.dtpr(Tte, fpred, links),
@@ -165,8 +183,18 @@ def main(argv=None):
         print(f"forest of {args.forest_trees} trees: cv geomean {forest_cv:.4f} (single tree {best['cv_geomean']:.4f}); "
               f"held-out accuracy {100 * forest_held['accuracy']:.1f}%  DTPR {forest_held['dtpr']:.4f}  "
               f"geomean {forest_held['geomean']:.4f}  leaves {fst['leaves']}")
-        if forest_cv > best["cv_geomean"]:
+        print(f"gate on M*N*K (tree below, forest at or above; {args.tree_ns:.0f} / {args.forest_ns:.0f} ns per evaluation "
+              "charged to every out-of-fold prediction):")
+        for r in gate_table:
+            print(f"  gate {r['gate']:>20d}  geomean incl. selector cost {r['geomean_with_cost']:.4f}  "
+                  f"({r['rows_by_tree']} of {Xtr.shape[0]} rows by the tree){'  <-- chosen' if r['gate'] == gate else ''}")
+        if gate < cart.INT64_MAX:
             forest = cand
+            gpred = cart.gated_predict(Xte, gate, pred, fpred)
+            gated_held = {"accuracy": cart.accuracy(gpred, cart.labels_from_table(Tte)), "dtpr": cart.dtpr(Tte, gpred, links),
+                          "geomean": cart.geomean_ratio(Tte, gpred, links)}
+            print(f"gated model on the held-out set: accuracy {100 * gated_held['accuracy']:.1f}%  DTPR {gated_held['dtpr']:.4f}  "
+                  f"geomean {gated_held['geomean']:.4f}")
 
     d_tiled, d_direct, d_thr = (meta[0]["id"], 0, 512.0 ** 3)
     if os.path.exists(args.cfg1):
@@ -177,12 +205,16 @@ def main(argv=None):
         name = f"{best['name']}/{best['leaf_rule']}"
         nested = tree.to_nested()
         forest_nested = forest.to_nested() if forest is not None else None
-        if forest is not None:
+        if forest is None:  # the tree alone, as nested if-then-else
+            shipped, style, st_ship = nested, "branches", st
+        elif gate == 0:
             name = f"forest{args.forest_trees}-{name}"
-            st_ship = forest.stats()
+            shipped, style, st_ship = forest_nested, "branches", forest.stats()
         else:
-            st_ship = st
-        codegen.write_header(forest_nested if forest is not None else nested, name, variant_names=tab["variants"],
+            name = f"gate2^{gate.bit_length() - 1}-forest{args.forest_trees}-{name}"
+            shipped, style = {"gate": gate, "tree": nested, "forest": forest_nested}, "branches"
+            st_ship = {"leaves": st["leaves"] + forest.stats()["leaves"], "height": max(st["height"], forest.stats()["height"])}
+        codegen.write_header(shipped, name, variant_names=tab["variants"], style=style,
                              default_tiled=d_tiled, default_direct=d_direct, default_threshold=d_thr,
                              provenance=f"model {name}, trained on {Xtr.shape[0]} inputs ("
                                         + ", ".join(f"{src.count(n)} {n}" for n in dict.fromkeys(sorted(src))) + "); "
@@ -194,10 +226,13 @@ def main(argv=None):
                        "cv_geomean": best["cv_geomean"], "heldout_at_training_time": held, "stats": st,
                        "variants": tab["variants"], "tree": nested, "forest": forest_nested,
                        "forest_trees": args.forest_trees if forest is not None else 0,
+                       "gate": gate if forest is not None else None, "gate_table": gate_table,
+                       "selector_ns_assumed": {"tree": args.tree_ns, "forest": args.forest_ns},
+                       "heldout_rows_excluded_from_extra_tables": True,
                        "forest_cv_geomean": forest_cv, "forest_heldout_at_training_time": forest_held,
                        "default_dispatch": {"tiled": d_tiled, "direct": d_direct, "threshold": d_thr},
                        "sweep_on_heldout": report,
-                       "cv_table": cv_table}, f, indent=1)
+                       "cv_table": cv_table}, f, separators=(",", ":"))
         print(f"wrote {codegen.GENERATED_HEADER} and results/model.json -- rebuild the library")
 
 

@@ -215,6 +215,21 @@ def config4(n_shapes=2000, max_flops=2 ** 32, seed=None):
     return [cases[i] for i in order]
 
 
+def fresh_shapes(n_shapes, seed_index=0, log2_max_dim=13.0, max_flops=2 ** 32, min_work=0):
+    """[n, 5] int64 rows (M, N, K, tA, tB) drawn like the random sweep (dimensions round(2**(log2_max_dim * u)),
+    the triple redrawn while 2 M N K > max_flops or M N K < min_work, fair-coin transposes), from a stream of its
+    own: shapes nobody has asked the selector about before, for timing its evaluation."""
+    rng = np.random.Generator(np.random.PCG64(case_seed(40, seed_index)))
+    rows = np.empty((0, 5), dtype=np.int64)
+    while rows.shape[0] < n_shapes:
+        d = np.rint(2.0 ** (log2_max_dim * rng.uniform(size=(2 * n_shapes, 3)))).astype(np.int64).clip(1, None)
+        work = d[:, 0] * d[:, 1] * d[:, 2]
+        d = d[(2 * work <= max_flops) & (work >= min_work)]
+        t = rng.integers(0, 2, size=(d.shape[0], 2))
+        rows = np.vstack([rows, np.column_stack([d, t])])
+    return rows[:n_shapes]
+
+
 def split_train_heldout(cases, train_fraction=0.8):
     """First 80 % of the (already shuffled) list trains, the rest is held out (Section 3, 'Datasets')."""
     n_train = int(round(train_fraction * len(cases)))

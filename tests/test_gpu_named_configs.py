@@ -42,10 +42,29 @@ def _check(case, variants=(None,)):
 _SQUARE = wl.config1()
 
 
-@pytest.mark.timeout(900)
+@pytest.mark.timeout(600)
 @pytest.mark.parametrize("idx", range(len(_SQUARE)), ids=[c.name for c in _SQUARE])
 def test_square_sweep_every_case_whole_matrix(idx):
-    _check(_SQUARE[idx])
+    from oracle import gemm_oracle as go
+    from tests import gpu_util as gu
+    case = _SQUARE[idx]
+    c = case.resolved()
+    if not (c.tA() and c.tB() and c.M >= 2048):
+        _check(case)
+        return
+    # Both operands transposed: the oracle then runs a dot product per element and walks B with a stride of a
+    # whole column, which takes twenty times as long as the other cases at these sizes.  It is handed a
+    # transposed copy of B with transB = none instead: op(B)(k, j) is the same number either way, every element
+    # is the same sum in the same order, so oracle_sgemm returns the same bits (the identity is one of the
+    # oracle's own pins).  The GPU still gets the original operands and both transposes.
+    assert c.layout == wl.COL_MAJOR and c.ldb == c.N
+    A, B, C0, outs = gu.run_case_many(c, [None])
+    st, got = outs[0]
+    assert st == 0, mdg.mdg_status_string(st)
+    Bt = np.ascontiguousarray(B.reshape(c.K, c.N).T).ravel()  # stored N x K (ld N)  ->  stored K x N (ld K)
+    ref = C0.copy()
+    assert go.sgemm(c.layout, c.transA, wl.NO_TRANS, c.M, c.N, c.K, c.alpha, A, c.lda, Bt, c.K, c.beta, ref, c.ldc) == 0
+    gu.check_against_oracle(c, got, A, B, C0, ref=ref)
 
 
 @pytest.mark.timeout(900)

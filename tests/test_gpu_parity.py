@@ -249,3 +249,33 @@ def test_split_k_is_repeatable_and_exact():
         torch.cuda.synchronize()
         for dC in outs:
             assert np.array_equal(dC.cpu().numpy(), ref), d["name"]
+
+
+@pytest.mark.parametrize("tA,tB", TT)
+def test_indirect_variants_pack_pad_and_match_the_oracle(tA, tB):
+    # the helper passes must zero-fill the padding they add, must not read the (NaN-poisoned) padding of the
+    # caller's leading dimensions, and an operand that already has the packed form is used where it lies
+    gu = _gu()
+    ind = [d for d in mdg.variants() if d["family"] == mdg.FAMILY_INDIRECT]
+    assert len(ind) >= 3
+    for d in ind:
+        bm, bn, bk = d["tile_m"], d["tile_n"], d["tile_k"]
+        shapes = [(2 * max(bm, 64), max(bn, 64), 3 * bk, 0),           # whole tiles: NT needs no copy at all
+                  (2 * max(bm, 64) - 5, max(bn, 64) + 3, 3 * bk + 1, 3),  # ragged in M, N and K, padded leading dimensions
+                  (7, 5, 3, 1), (1, 300, 70, 0)]
+        for M, N, K, pad in shapes:
+            base = GemmCase(M, N, K, tA, tB, 1.5, -0.5, dist="smallint", c0="smallint",
+                            seed=wl.case_seed(16, M + N + K), name=f"indirect/{d['name']}/{M}x{N}x{K}/{tA}{tB}").resolved()
+            case = GemmCase(**{**base.__dict__, "lda": base.lda + pad, "ldb": base.ldb + pad, "ldc": base.ldc + pad})
+            assert d["id"] in gu.legal_variants(case)
+            st, got, A, B, C0 = gu.run_case(case, variant=d["id"])
+            assert st == 0, (d["name"], mdg.mdg_status_string(st))
+            gu.check_against_oracle(case, got, A, B, C0, exact=True)
+    # without a workspace a transposed operand cannot be packed: refused when forced, replaced by the plain tile in mdg_sgemm
+    case = GemmCase(300, 200, 100, TR, NT, 1.0, 0.0, seed=3).resolved()
+    assert mdg.mdg_set_workspace(0, 0) == 0
+    try:
+        assert gu.run_case(case, variant=ind[0]["id"])[0] == mdg.ERR_WORKSPACE
+    finally:
+        ws = gu._WS["t"]
+        assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0

@@ -26,7 +26,7 @@ def test_variant_table_is_consistent():
     assert len({v["name"] for v in vs}) == len(vs)
     assert vs[0]["family"] == mdg.FAMILY_DIRECT and vs[0]["split_k"] == 1
     fams = {v["family"] for v in vs}
-    assert fams == {mdg.FAMILY_DIRECT, mdg.FAMILY_TILED, mdg.FAMILY_SKINNY}
+    assert fams == {mdg.FAMILY_DIRECT, mdg.FAMILY_TILED, mdg.FAMILY_SKINNY, mdg.FAMILY_INDIRECT}
     for v in vs:
         assert v["id"] == vs.index(v)
         assert v["threads"] in (64, 128, 256, 512, 1024) and v["split_k"] >= 1
@@ -53,6 +53,9 @@ def test_fallback_chains_end_at_variant_zero_and_only_relax_the_variant():
             nxt = vs[x["fallback"]]
             if x["family"] == mdg.FAMILY_TILED and x["split_k"] > 1:  # fewer K slices of the same tile
                 assert nxt["family"] == x["family"] and nxt["split_k"] < x["split_k"]
+                assert (nxt["tile_m"], nxt["tile_n"], nxt["tile_k"]) == (x["tile_m"], x["tile_n"], x["tile_k"])
+            elif x["family"] == mdg.FAMILY_INDIRECT:  # the same tile without the helper passes
+                assert nxt["family"] == mdg.FAMILY_TILED and nxt["split_k"] == 1
                 assert (nxt["tile_m"], nxt["tile_n"], nxt["tile_k"]) == (x["tile_m"], x["tile_n"], x["tile_k"])
             elif x["family"] == mdg.FAMILY_SKINNY:  # wider with the same split, else fewer slices, else a tile
                 assert (nxt["family"] == mdg.FAMILY_SKINNY and nxt["sub_n"] > x["sub_n"] and nxt["split_k"] == x["split_k"]) or \
@@ -112,6 +115,9 @@ def test_legality_rules():
     mdg.mdg_set_workspace(0, 0)
     for v in vs:
         need = mdg.mdg_workspace_bytes(v["id"], 100, 50, 4096)
+        if v["family"] == mdg.FAMILY_INDIRECT:  # padded copies of both operands (see the test of the indirect variants)
+            assert need > 4 * (100 + 50) * 4096
+            continue
         assert need == (v["split_k"] * 100 * 50 * 4 if v["split_k"] > 1 else 0)
         if v["split_k"] > 1:
             assert mdg.mdg_variant_legal(v["id"], 0, 0, 100, 4, 4096, 100, 4096, 100) == 0  # no workspace registered
@@ -202,3 +208,30 @@ def test_workspace_registration_errors_have_their_own_code():
     assert mdg.mdg_variant_legal(sk, 0, 0, 128, 128, 4096, 128, 4096, 128) == 1
     assert mdg.mdg_set_workspace(0, 0) == 0
     assert mdg.mdg_variant_legal(sk, 0, 0, 128, 128, 4096, 128, 4096, 128) == 0
+
+
+def test_indirect_variants_need_workspace_for_the_packed_copies_only():
+    vs = mdg.variants()
+    ind = [v for v in vs if v["family"] == mdg.FAMILY_INDIRECT]
+    assert len(ind) >= 3
+    for v in ind:
+        bm, bn, bk = v["tile_m"], v["tile_n"], v["tile_k"]
+        qm, qn = max(bm, 64), max(bn, 64)
+        M, N, K = 3 * qm, 2 * qn, 5 * bk
+        assert mdg.mdg_set_workspace(0, 0) == 0
+        # operands already in packed form (A not transposed, B transposed, whole tiles): no copy, no workspace
+        assert mdg.mdg_variant_legal(v["id"], 0, 1, M, N, K, M, N, M) == 1
+        # a transposed A must be copied: illegal without workspace, legal with enough of it
+        assert mdg.mdg_variant_legal(v["id"], 1, 1, M, N, K, K, N, M) == 0
+        assert mdg.mdg_set_workspace(4096, 4 * M * K) == 0
+        assert mdg.mdg_variant_legal(v["id"], 1, 1, M, N, K, K, N, M) == 1
+        assert mdg.mdg_variant_legal(v["id"], 1, 0, M, N, K, K, K, M) == 0  # now B needs a copy as well
+        # ragged sizes are padded to whole tiles (and to multiples of 64 for the transposing helper)
+        Mr, Nr, Kr = M - 1, N - 3, K - 1
+        need = 4 * (M * K + N * K)
+        assert mdg.mdg_workspace_bytes(v["id"], Mr, Nr, Kr) == need
+        assert mdg.mdg_set_workspace(4096, need - 4) == 0
+        assert mdg.mdg_variant_legal(v["id"], 0, 1, Mr, Nr, Kr, Mr, Nr, Mr) == 0
+        assert mdg.mdg_set_workspace(4096, need) == 0
+        assert mdg.mdg_variant_legal(v["id"], 0, 1, Mr, Nr, Kr, Mr, Nr, Mr) == 1
+    assert mdg.mdg_set_workspace(0, 0) == 0

@@ -345,3 +345,33 @@ def test_forest_of_identical_full_samples_predicts_like_its_tree_when_leaves_are
     forest = so.fit_forest(X, y, T, [whole, whole, whole], None, 1, "majority", 0)
     assert [so.predict_forest(forest, x, 5) for x in X] == y
     assert so.geomean_ratio(T, [so.predict_forest(forest, x, 5) for x in X]) == 1.0
+
+
+def test_gated_model_and_gate_choice_worked_out_by_hand():
+    # two inputs, two variants.  Input A is small (work 8), input B is large (work 10^9).
+    #   times (seconds)      v0        v1
+    #   A                    4e-6      2e-6      best v1
+    #   B                    2e-3      1e-3      best v1
+    # the 'tree' always answers v0 except it is right on A; the 'forest' is right on both.
+    tree = {"feature": 6, "threshold": 100, "n": 2, "left": {"leaf": 1, "n": 1}, "right": {"leaf": 0, "n": 1}}
+    forest = [{"leaf": 1, "n": 2, "ids": [1, 0], "costs": [0, 700000], "rest": 700000}]
+    xa, xb = so.expand_features((2, 2, 2, 0, 0)), so.expand_features((1000, 1000, 1000, 0, 0))
+    assert xa[6] == 8 and xb[6] == 10 ** 9
+    assert so.predict_gated(tree, forest, 9, xa, 2) == so.predict(tree, xa) == 1          # below the gate: the tree
+    assert so.predict_gated(tree, forest, 8, xa, 2) == so.predict_forest(forest, xa, 2) == 1  # at the gate: the forest
+    assert so.predict_gated(tree, forest, 10 ** 9 + 1, xb, 2) == 0 and so.predict_gated(tree, forest, 10 ** 9, xb, 2) == 1
+    times = [[4e-6, 2e-6], [2e-3, 1e-3]]
+    # selector costs: tree 0 ns, forest 2000 ns.  Ratios t_best / (t_pred + c):
+    #   gate 0   (forest, forest): A 2e-6 / 4e-6 = 0.5       B 1e-3 / 1.002e-3
+    #   gate 100 (tree, forest)  : A 2e-6 / 2e-6 = 1         B 1e-3 / 1.002e-3       <- best
+    #   gate inf (tree, tree)    : A 1                        B 1e-3 / 2e-3 = 0.5
+    assert so.ratio_with_selector_cost(times[0], 1, 2000e-9) == pytest.approx(0.5)
+    assert so.ratio_with_selector_cost(times[1], 0, 0.0) == pytest.approx(0.5)
+    g, score = so.choose_gate([xa, xb], times, [1, 0], [1, 1], 0.0, 2000.0, (0, 100, 2 ** 63 - 1))
+    assert g == 100 and score == pytest.approx(math.sqrt(1.0 * (1e-3 / 1.002e-3)))
+    # a forest as cheap as the tree wins everywhere: first maximum in candidate order is gate 0
+    g, score = so.choose_gate([xa, xb], times, [1, 0], [1, 1], 0.0, 0.0, (0, 100, 2 ** 63 - 1))
+    assert g == 0 and score == pytest.approx(1.0)
+    # a forest that costs ten milliseconds per evaluation never pays (B: 1e-3 / 11e-3 < 0.5): the tree alone
+    g, _ = so.choose_gate([xa, xb], times, [1, 0], [1, 1], 0.0, 1e7, (0, 100, 2 ** 63 - 1))
+    assert g == 2 ** 63 - 1

@@ -124,13 +124,14 @@ def _compile_selector(header_text, tmp_path):
     return L
 
 
+@pytest.mark.parametrize("style", ["branches", "table"])
 @pytest.mark.parametrize("H,L,rule", [(None, 1, "majority"), (4, 2, "logratio"), (0, 1, "majority")])
-def test_generated_cpp_equals_the_tree_everywhere(H, L, rule, tmp_path):
+def test_generated_cpp_equals_the_tree_everywhere(H, L, rule, style, tmp_path):
     X, T, _, _ = _table(260, 11, 5)
     tree = cart.fit_cart(X, T, H, L, rule)
     nested = tree.to_nested()
     text = codegen.tree_to_cpp(nested, "test-model", variant_names=[f"v{i}" for i in range(11)], default_tiled=3,
-                               default_direct=1)
+                               default_direct=1, style=style)
     lib = _compile_selector(text, tmp_path)
     assert lib.name() == b"test-model" and lib.dflt(0) == 3 and lib.dflt(1) == 1
     # all training shapes plus threshold-1 / threshold / threshold+1 probes of every internal node
@@ -180,6 +181,43 @@ def test_forest_is_identical_to_the_oracle_and_to_its_generated_code(seed, n, v,
         assert got == [so.predict_forest(ref, so.expand_features(tuple(int(x) for x in p)), v) for p in P]
 
 
+def test_gated_model_and_its_gate_are_identical_to_the_oracle_and_to_the_generated_code(tmp_path):
+    X, T, Xl, Tl = _table(320, 10, 31)
+    ntr = 260
+    boot = wl.bootstrap_indices(ntr, 4)
+    tree = cart.fit_cart(X[:ntr], T[:ntr], None, 4, "logratio", 0)
+    forest = cart.fit_forest(X[:ntr], T[:ntr], boot, None, 4, "logratio", 0)
+    nested_tree, nested_forest = tree.to_nested(), forest.to_nested()
+    pt, pf = tree.predict(X), forest.predict(X)
+    assert (pt != pf).sum() > 10  # the two models disagree often enough for the gate to matter
+    # gate choice: same candidate set, same costs -> same gate and score as the plain-Python oracle
+    gates = (0, 1 << 12, 1 << 18, 1 << 22, 1 << 26, 1 << 30, cart.INT64_MAX)
+    for tree_ns, forest_ns in ((30.0, 500.0), (30.0, 30.0), (0.0, 5e4)):
+        g, table = cart.choose_gate(X, T, pt, pf, tree_ns, forest_ns, 0, gate_set=gates)
+        g_ref, score_ref = so.choose_gate(Xl, Tl, pt.tolist(), pf.tolist(), tree_ns, forest_ns, gates, 0)
+        assert g == g_ref
+        assert max(r["geomean_with_cost"] for r in table) == pytest.approx(score_ref, rel=1e-12)
+    # with a free selector the cost-inclusive score of a forest-only gate is the plain geomean ratio
+    _, table = cart.choose_gate(X, T, pt, pf, 0.0, 0.0, 0, gate_set=(0, cart.INT64_MAX))
+    assert table[0]["geomean_with_cost"] == pytest.approx(cart.geomean_ratio(T, pf, 0), rel=1e-12)
+    assert table[1]["geomean_with_cost"] == pytest.approx(cart.geomean_ratio(T, pt, 0), rel=1e-12)
+    # generated code of the gated pair == product == oracle, also right at the gate
+    gate = 1 << 18
+    text = codegen.tree_to_cpp({"gate": gate, "tree": nested_tree, "forest": nested_forest}, "test-gated",
+                               variant_names=[f"v{i}" for i in range(10)])
+    lib = _compile_selector(text, tmp_path)
+    probes = [tuple(r) for r in X.tolist()] + [(gate - 1, 1, 1, 0, 0), (gate, 1, 1, 0, 0), (gate + 1, 1, 1, 1, 1),
+                                                 (1 << 9, 1 << 9, 1, 0, 1), (1 << 9, 1 << 9, 2, 1, 0), (511, 512, 1, 0, 0)]
+    for f, thr in codegen.internal_thresholds({"gate": gate, "tree": nested_tree, "forest": nested_forest})[::7]:
+        probes += [_probe(f, max(thr + d, 0), base=tuple(X[0].tolist())) for d in (-1, 0, 1)]
+    P = np.array(probes, dtype=np.int64)
+    got = [lib.sel(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) for p in P]
+    assert got == cart.gated_predict(P, gate, tree.predict(P), forest.predict(P)).tolist()
+    assert got == [so.predict_gated(nested_tree, nested_forest, gate, so.expand_features(tuple(int(a) for a in p)), 10) for p in P]
+    sides = {int(p[0]) * int(p[1]) * int(p[2]) < gate for p in P}
+    assert sides == {True, False}
+
+
 def test_forest_cross_validation_is_seeded_and_bounded():
     X, T, _, _ = _table(260, 9, 11)
     boot_for = lambda n: wl.bootstrap_indices(n, 4)  # noqa: E731
@@ -212,13 +250,24 @@ def test_shipped_selector_matches_the_stored_model():
         pytest.skip("no trained model stored yet")
     model = json.load(open(path))
     assert mdg.mdg_selector_name() == model["name"]
-    assert model["variants"] == [v["name"] for v in mdg.variants()]
+    # the model was trained on the variant table as it stood; variants added since sit behind those it knows
+    assert model["variants"] == [v["name"] for v in mdg.variants()][:len(model["variants"])]
     rng = np.random.default_rng(6)
     P = np.column_stack([np.rint(2.0 ** (13 * rng.uniform(size=(3000, 3)))).astype(np.int64),
                          rng.integers(0, 2, size=(3000, 2))])
     extra = []
-    shipped = model.get("forest") or model["tree"]  # a list of trees with cost lists, or one tree
+    # what ships: the tree alone, the forest alone (gate 0), or the gated pair
     n_var = len(model["variants"])
+    gate = model.get("gate")
+    if not model.get("forest"):
+        shipped = model["tree"]
+        want_of = lambda x: so.predict(shipped, x)  # noqa: E731
+    elif gate in (None, 0):
+        shipped = model["forest"]
+        want_of = lambda x: so.predict_forest(shipped, x, n_var)  # noqa: E731
+    else:
+        shipped = {"gate": gate, "tree": model["tree"], "forest": model["forest"]}
+        want_of = lambda x: so.predict_gated(model["tree"], model["forest"], gate, x, n_var)  # noqa: E731
     thresholds = codegen.internal_thresholds(shipped)
     if len(thresholds) > 4000:  # a forest has tens of thousands of nodes: probe a seeded sample of them
         thresholds = [thresholds[i] for i in rng.choice(len(thresholds), 4000, replace=False)]
@@ -226,10 +275,12 @@ def test_shipped_selector_matches_the_stored_model():
         for d in (-1, 0, 1):
             extra.append(_probe(f, max(0, thr + d)))
     P = np.vstack([P, np.array(extra, dtype=np.int64).reshape(-1, 5)])
+    if gate not in (None, 0):  # both sides of the gate, and the gate itself
+        extra += [(gate - 1, 1, 1, 0, 0), (gate, 1, 1, 0, 0), (2048, 2048, 2048, 0, 1), (4096, 4096, 4096, 1, 0), (8192, 8192, 8192, 0, 0)]
+        P = np.vstack([P, np.array(extra[-5:], dtype=np.int64)])
     for p in P:
         x = so.expand_features(tuple(int(a) for a in p))
-        want = so.predict_forest(shipped, x, n_var) if isinstance(shipped, list) else so.predict(shipped, x)
-        assert mdg.mdg_select(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) == want
+        assert mdg.mdg_select(int(p[3]), int(p[4]), int(p[0]), int(p[1]), int(p[2])) == want_of(x)
     d = model["default_dispatch"]
     assert mdg.mdg_select_default(0, 0, 4096, 4096, 4096) == d["tiled"]
     assert mdg.mdg_select_default(0, 0, 8, 8, 8) == d["direct"]
@@ -243,8 +294,9 @@ def test_training_union_keeps_evaluation_shapes_out_and_is_seeded():
     extra = {"X": np.vstack([Xe, X4[90:95]]), "T": np.vstack([Te, T4[90:95]])}
     banned = {"X": Xe[:7], "T": Te[:7]}
     X, T, src = train.training_union(tab4, [("grid", extra)], [banned])
-    # 80 rows of the sweep + 45 extra rows minus the 7 banned shapes
-    assert X.shape[0] == 80 + 45 - 7 and src.count("cfg4") == 80 and src.count("grid") == 38
+    # 80 rows of the sweep + 45 extra rows minus the 7 banned shapes and the 5 that repeat held-out shapes
+    assert X.shape[0] == 80 + 45 - 7 - 5 and src.count("cfg4") == 80 and src.count("grid") == 33
+    assert not ({tuple(r[:3]) for r in X4[80:].tolist()} & {tuple(r[:3]) for r in X.tolist()})  # no held-out shape leaks in
     have = {tuple(r[:3]) for r in X.tolist()}
     assert not ({tuple(r[:3]) for r in Xe[:7].tolist()} & have)
     # the held-out 20 % of the sweep never enters through the sweep itself
