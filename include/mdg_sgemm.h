@@ -62,7 +62,8 @@ enum {
   MDG_ERR_LAUNCH = -103,          /* the HIP runtime rejected a launch or an event call */
   MDG_ERR_BAD_VARIANT = -104,     /* variant id out of range */
   MDG_ERR_NULL = -105,            /* a required output pointer is NULL */
-  MDG_ERR_ALIGNMENT = -106        /* a workspace pointer is not 256-byte aligned */
+  MDG_ERR_ALIGNMENT = -106,       /* a workspace pointer is not 256-byte aligned */
+  MDG_ERR_SCRATCH_LIMIT = -107    /* mdg_sgemm_static_scratch: the variant needs more than MDG_STATIC_SCRATCH_BYTES */
 };
 
 /* Kernel families (Section 2.3: one generic kernel plus one specialised kernel; the vector-shaped
@@ -114,6 +115,29 @@ int mdg_sgemm(int layout, int transA, int transB, int64_t M, int64_t N, int64_t 
 int mdg_sgemm_variant(int variant, int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
                       const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
                       void* stream);
+
+/*
+ * mdg_sgemm for callers that cannot allocate device memory and have registered no workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result.  The
+ * partial sums of split-K variants (and the packed operand copies of indirect variants) go to a device array
+ * of MDG_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library is used on holds its own copy until the process ends) instead
+ * of the registered workspace, which this call neither reads nor needs.  The call allocates and frees nothing.
+ *
+ * The variant is the one mdg_sgemm would run with a workspace that is never too small.  If that variant needs
+ * more than MDG_STATIC_SCRATCH_BYTES (mdg_workspace_bytes: split_k * M * N * 4 bytes for a split-K variant), the
+ * call returns MDG_ERR_SCRATCH_LIMIT and
+ * enqueues nothing; C is untouched.  Variants that do not split K need no scratch and always run.
+ *
+ * All calls on one GPU share that GPU's array: calls on different streams (or from different threads) that may
+ * execute at the same time race on it, exactly as calls sharing a registered workspace do; calls on one stream
+ * are ordered and safe.  Nothing in the array has to be cleared between calls (every element a call reads, it
+ * has written first).  The device address of the array is looked up on the first call on each device, with
+ * that device current.
+ */
+#define MDG_STATIC_SCRATCH_BYTES (32 << 20)
+int mdg_sgemm_static_scratch(int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+                             const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C,
+                             int64_t ldc, void* stream);
 
 /*
  * The compiled decision tree (Section 3, 'Model and code generation'): pure

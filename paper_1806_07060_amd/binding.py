@@ -17,6 +17,8 @@ NO_TRANS, TRANS, CONJ_TRANS = 111, 112, 113
 
 OK = 0
 ERR_WORKSPACE, ERR_ILLEGAL_VARIANT, ERR_LAUNCH, ERR_BAD_VARIANT, ERR_NULL, ERR_ALIGNMENT = -101, -102, -103, -104, -105, -106
+ERR_SCRATCH_LIMIT = -107
+STATIC_SCRATCH_BYTES = 32 << 20  # MDG_STATIC_SCRATCH_BYTES
 
 FAMILY_DIRECT, FAMILY_TILED, FAMILY_SKINNY, FAMILY_INDIRECT = 0, 1, 2, 3
 FAMILY_NAMES = {0: "direct", 1: "tiled", 2: "skinny", 3: "indirect"}
@@ -26,7 +28,8 @@ MAX_DIM = 2 ** 31 - 1 - 65536  # MDG_MAX_DIM
 # every symbol include/mdg_sgemm.h declares
 EXPORTS = ("mdg_sgemm", "mdg_sgemm_variant", "mdg_select", "mdg_select_default", "mdg_selector_name",
            "mdg_variant_count", "mdg_variant_info", "mdg_variant_legal", "mdg_workspace_bytes", "mdg_set_workspace",
-           "mdg_status_string", "mdg_time_calls", "mdg_time_select_ns", "mdg_select_memo", "mdg_time_select_memo_ns")
+           "mdg_status_string", "mdg_time_calls", "mdg_time_select_ns", "mdg_select_memo", "mdg_time_select_memo_ns",
+           "mdg_sgemm_static_scratch")
 
 
 class VariantDesc(ctypes.Structure):
@@ -55,6 +58,7 @@ def lib():
     gemm = [ci, ci, ci, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp]
     L.mdg_sgemm.argtypes, L.mdg_sgemm.restype = gemm, ci
     L.mdg_sgemm_variant.argtypes, L.mdg_sgemm_variant.restype = [ci] + gemm, ci
+    L.mdg_sgemm_static_scratch.argtypes, L.mdg_sgemm_static_scratch.restype = gemm, ci
     L.mdg_select.argtypes, L.mdg_select.restype = [ci, ci, i64, i64, i64], ci
     L.mdg_select_default.argtypes, L.mdg_select_default.restype = [ci, ci, i64, i64, i64], ci
     L.mdg_select_memo.argtypes, L.mdg_select_memo.restype = [ci, ci, i64, i64, i64], ci
@@ -79,6 +83,11 @@ def lib():
 
 def mdg_sgemm(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=0):
     return int(lib().mdg_sgemm(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream))
+
+
+def mdg_sgemm_static_scratch(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=0):
+    return int(lib().mdg_sgemm_static_scratch(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc,
+                                              stream))
 
 
 def mdg_sgemm_variant(variant, layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=0):

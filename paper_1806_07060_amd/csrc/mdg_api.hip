@@ -1,9 +1,44 @@
 // C-ABI entry points that enqueue GPU work: the GEMM call, the forced-variant call and the event-timing core of
 // the tuning run.  Validation, selection and legality are host code in mdg_dispatch.cpp; the kernels live in
 // mdg_direct.hip, mdg_tiled.hip and mdg_skinny.hip.
+#include <atomic>
+#include <mutex>
+
 #include "mdg_internal.h"
 
 namespace mdg {
+
+// ---- scratch memory of the allocation-free entry point --------------------------------------------------
+// A file-scope device array stands in for the registered workspace (split-K partial sums).  Every GPU the
+// library runs on holds its own copy at its own address until the process ends; the name below is only a
+// host-side handle, the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) float scratch[MDG_STATIC_SCRATCH_BYTES / sizeof(float)];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<float*> g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+static int scratch_on_current_device(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MDG_ERR_LAUNCH;
+  float* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (p == nullptr) {
+      void* sym = nullptr;
+      if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || sym == nullptr) {
+        (void)hipGetLastError();
+        return MDG_ERR_LAUNCH;
+      }
+      p = static_cast<float*>(sym);
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return MDG_OK;
+}
 
 static int run_variant(const VariantEntry& e, const GemmArgs& g) {
   switch (e.desc.family) {
@@ -65,6 +100,28 @@ int mdg_sgemm_variant(int variant, int layout, int transA, int transB, int64_t M
   const VariantEntry& e = variant_table(nullptr)[variant];
   if (workspace_need(e, g.tA, g.tB, g.M, g.N, g.K) > g.ws_bytes) return MDG_ERR_WORKSPACE;
   if (!legal(e, g)) return MDG_ERR_ILLEGAL_VARIANT;
+  return run_variant(e, g);
+}
+
+int mdg_sgemm_static_scratch(int layout, int transA, int transB, int64_t M, int64_t N, int64_t K, float alpha,
+                             const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C,
+                             int64_t ldc, void* stream) {
+  GemmArgs g;
+  // choose as mdg_sgemm would with a workspace that is never too small ...
+  int st = canonicalise(layout, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, nullptr,
+                        ~(size_t)0, &g);
+  if (st != MDG_OK) return st;
+  if (handled_without_gemm(g, &st)) return st;
+  const VariantEntry& e = variant_table(nullptr)[choose_variant(g, SEL_TREE)];
+  // ... and refuse, before anything is enqueued, what does not fit the static array
+  const size_t need = workspace_need(e, g.tA, g.tB, g.M, g.N, g.K);
+  if (need > (size_t)MDG_STATIC_SCRATCH_BYTES) return MDG_ERR_SCRATCH_LIMIT;
+  g.ws_bytes = 0;
+  if (need > 0) {
+    st = scratch_on_current_device(&g.ws);
+    if (st != MDG_OK) return st;
+    g.ws_bytes = MDG_STATIC_SCRATCH_BYTES;
+  }
   return run_variant(e, g);
 }
 
