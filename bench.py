@@ -54,7 +54,8 @@ def kernel_symbol(desc, tA, tB):
     if desc["family"] in (1, 3):
         wgm, wgn = desc["tile_m"] // desc["sub_m"], desc["tile_n"] // desc["sub_n"]
         wgk = desc["threads"] // (64 * wgm * wgn)
-        return f"tiled_kernel<{desc['tile_m']}, {desc['tile_n']}, {desc['tile_k']}, {wgm}, {wgn}, {wgk}, {b(tA)}, {b(tB)}>"
+        return (f"tiled_kernel<{desc['tile_m']}, {desc['tile_n']}, {desc['tile_k']}, {wgm}, {wgn}, {wgk}, {b(tA)}, {b(tB)}, "
+                f"{b(desc['lds'] == 2)}, {2 if '_km' not in desc['name'] else desc['name'].split('_km')[1][0]}>")
     if desc["family"] == 0:
         return f"direct_kernel<{desc['sub_m']}, {desc['sub_n']}, {b(desc['lds'])}, {b(tA)}, {b(tB)}>"
     if desc["name"].startswith("skinny_mfma"):  # last argument: 16-byte loads, the case for aligned operands

@@ -89,7 +89,8 @@ typedef struct {
   int32_t sub_m;       /* direct: rows per thread; tiled: rows per wave; skinny: rows per thread */
   int32_t sub_n;       /* direct: columns per thread; tiled: columns per wave; skinny: columns held per thread */
   int32_t vec;         /* widest global access in fp32 elements */
-  int32_t lds;         /* 1 if operands are staged through LDS */
+  int32_t lds;         /* 1 if operands are staged through LDS; 2 if row-contiguous operands are moved from global
+                          memory straight into LDS (needs those operands 16-byte aligned) */
   int32_t split_k;     /* number of K slices (1 = none); > 1 needs workspace and a reduce pass */
   int32_t fallback;    /* variant tried next when this one is not legal for an input (chains end at a variant that is) */
   char name[48];

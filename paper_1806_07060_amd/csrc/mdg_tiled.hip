@@ -27,10 +27,13 @@
 // non-contracted index contiguous).  Global loads are float4 along whichever
 // index is contiguous in memory (also for operands that are only 4-byte
 // aligned); operands stored with k contiguous are transposed on their way into
-// LDS: the four lanes of a quad hold four neighbouring rows, exchange their
-// 4 x 4 block with two rounds of cross-lane moves, and each lane then writes one
-// 16-byte vector along the LDS row (with the +4 padding the sixteen rows a
-// group of lanes writes fall on distinct banks: no bank conflicts).  One barrier
+// LDS with four 4-byte writes per float4.  A half-wave holds sixteen
+// neighbouring rows of two neighbouring 16-byte k pieces: with the +4 row
+// padding the 64 lanes of each such write fall on 64 distinct banks, and each
+// half-wave on 32 distinct banks modulo 32 (no bank conflicts, checked with the
+// LDS conflict counter).  Cross-lane transposes that would
+// allow 16-byte writes were built and measured slower: vector-ALU work inside
+// this loop costs matrix-pipe time, LDS instructions do not.  One barrier
 // per K step; global loads run two K steps ahead (two register sets), LDS stages
 // alternate.
 #include <type_traits>
@@ -92,31 +95,6 @@ struct TiledParams {
   int a_vec, b_vec;  // 1 if float4 global loads of that operand are aligned
 };
 
-// Value of `x` in the lane whose index within its quad differs in bit 0 (xor1) / bit 1 (xor2).
-__device__ __forceinline__ float quad_xor1(float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float quad_xor2(float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true));
-}
-// 4 x 4 transpose across the four lanes of a quad: lane t enters with row t (elements 0..3) and leaves with
-// column t.  Two rounds that each swap one index bit between "lane" and "element"; b0 / b1 = bit 0 / 1 of the
-// lane's index in its quad.  All lanes of the quad must be active.
-__device__ __forceinline__ void quad_transpose(floatx4& r, bool b0, bool b1) {
-  {
-    const float s0 = b0 ? r[0] : r[1], s1 = b0 ? r[2] : r[3];
-    const float g0 = quad_xor1(s0), g1 = quad_xor1(s1);
-    r[0] = b0 ? g0 : r[0], r[1] = b0 ? r[1] : g0;
-    r[2] = b0 ? g1 : r[2], r[3] = b0 ? r[3] : g1;
-  }
-  {
-    const float s0 = b1 ? r[0] : r[2], s1 = b1 ? r[1] : r[3];
-    const float g0 = quad_xor2(s0), g1 = quad_xor2(s1);
-    r[0] = b1 ? g0 : r[0], r[2] = b1 ? r[2] : g0;
-    r[1] = b1 ? g1 : r[1], r[3] = b1 ? r[3] : g1;
-  }
-}
-
 constexpr int kPad = 4;
 constexpr int kGroupM = 8;  // tiles per group along M in the tile ordering
 
@@ -124,23 +102,45 @@ constexpr int kGroupM = 8;  // tiles per group along M in the tile ordering
 //   KMAJOR = stored with k contiguous:  X[k + mn * ld]   else   X[mn + k * ld]
 // `inside` (work-group uniform) = whole tile in range: 16-byte loads, through the aligned or the 4-byte-aligned
 // vector type (`aligned`, uniform too); otherwise element-wise guarded loads.
-template <int BMN, int BK, int NT, bool KMAJOR>
+//   DIRECT = the interior loop moves this operand from global memory straight into LDS (no registers, no LDS
+//            store instruction).  Such a load writes the 64 x 16 bytes of a wave to one contiguous kilobyte, so
+//            the stage is laid out in pieces of 256 floats (whole rows of the tile, in slot order) kPad floats
+//            apart instead of in padded rows; only for operands whose rows are contiguous in memory.
+//   KMAP   = which lane of a wave loads which 16-byte piece of a k-contiguous operand (see coords)
+template <int BMN, int BK, int NT, bool KMAJOR, bool DIRECT = false, int KMAP = 2>
 struct OperandLoader {
   static constexpr int kSlots = BMN * BK / 4 / NT;
   static_assert(BMN * BK % (4 * NT) == 0, "tile must split evenly into float4 slots");
+  static_assert(!(DIRECT && KMAJOR), "direct loads keep the memory order: rows of the non-contracted index only");
+  static_assert(!DIRECT || (256 % BMN == 0 && NT % 64 == 0), "a wave load must cover whole rows");
+  static constexpr int kPiece = 256 + kPad;         // floats from one wave load's kilobyte to the next
+  static constexpr int kRowsPerPiece = 256 / BMN;    // (DIRECT) tile rows per piece
+  // floats per LDS stage
+  static constexpr int kStage = DIRECT ? (BMN * BK / 256) * kPiece : BK * (BMN + kPad);
+  // float offset of row k (of a stage) in LDS; columns follow contiguously
+  __host__ __device__ static constexpr int row_offset(int k) {
+    return DIRECT ? (k / kRowsPerPiece) * kPiece + (k % kRowsPerPiece) * BMN : k * (BMN + kPad);
+  }
 
   // Slot -> (non-contracted index, k) of the first of its four elements.
   //   MN-major: consecutive lanes run along mn (one k row per BMN/4 lanes).
-  //   K-major : a wave covers 16 mn x 16 k: the four lanes of a quad take four neighbouring mn rows (so
-  //             that they can transpose their 4 x 4 block among themselves before the LDS store), the
-  //             quads step through the four 16-byte pieces of a 64-byte row piece, then through the mn
-  //             rows; further waves / slots take the other 16-wide k chunks and mn ranges.
+  //   K-major : a wave covers 16 mn x 16 k, i.e. sixteen row pieces of 64 bytes, each four 16-byte pieces long;
+  //             further waves / slots take the other 16-wide k chunks and mn ranges.  Which lane takes which
+  //             piece decides how the wave's global load coalesces and on which banks its four transposing
+  //             4-byte LDS writes per piece fall (bank = 16 * piece + 4 * e + row, modulo the bank count):
+  //               KMAP 0: lanes 4 i .. 4 i + 3 the four pieces of row i (64 contiguous bytes per lane quad;
+  //                       the two halves of a wave write the same banks modulo 32);
+  //               KMAP 1: lanes 16 j .. 16 j + 15 piece j of the sixteen rows (every write on distinct banks);
+  //               KMAP 2: lanes 2 i, 2 i + 1 of the first half-wave pieces 0, 1 of row i, of the second
+  //                       half-wave pieces 2, 3 (32 contiguous bytes per lane pair; distinct banks).
   __device__ __forceinline__ static void coords(int slot, int tid, int& mn, int& k) {
     int v = tid + slot * NT;
     if (KMAJOR) {
-      const int l = v & 63, chunk = v >> 6, q = l >> 2;
-      k = (chunk % (BK / 16)) * 16 + (q & 3) * 4;
-      mn = (chunk / (BK / 16)) * 16 + (q >> 2) * 4 + (l & 3);
+      const int l = v & 63, chunk = v >> 6;
+      const int piece = KMAP == 0 ? (l & 3) : KMAP == 1 ? (l >> 4) : (l & 1) + 2 * (l >> 5);
+      const int row = KMAP == 0 ? (l >> 2) : KMAP == 1 ? (l & 15) : (l >> 1) & 15;
+      k = (chunk % (BK / 16)) * 16 + piece * 4;
+      mn = (chunk / (BK / 16)) * 16 + row;
     } else {
       mn = (v % (BMN / 4)) * 4;
       k = v / (BMN / 4);
@@ -223,24 +223,36 @@ struct OperandLoader {
     }
   }
 
-  // registers -> LDS stage S[BK][BMN + kPad]
-  __device__ __forceinline__ static void store(const floatx4 (&r)[kSlots], float* S, int tid) {
-    constexpr int LD = BMN + kPad;
+  // global memory -> LDS stage S, all slots, no registers (interior tiles, 16-byte aligned operands).  Lane i
+  // of a wave writes bytes [16 i, 16 i + 16) of the piece; the piece address must be the same for all lanes.
+  __device__ __forceinline__ static void direct_load(const char* base, const uint32_t (&off)[kSlots], float* S, int wave) {
 #pragma unroll
-    for (int s = 0; s < kSlots; ++s) {
-      int mn, k;
-      coords(s, tid, mn, k);
-      if (KMAJOR) {
-        // lane t of the quad holds X(mn - t + 0..3 -> its own row mn, k .. k+3); after the transpose it holds
-        // k + t of the quad's four rows: one 16-byte store along the LDS row k + t
-        const int t = tid & 3;
-        floatx4 c = r[s];
-        quad_transpose(c, (t & 1) != 0, (t & 2) != 0);
-        *reinterpret_cast<floatx4*>(&S[(k + t) * LD + (mn - t)]) = c;
-      } else {
-        *reinterpret_cast<floatx4*>(&S[k * LD + mn]) = r[s];
-      }
+    for (int s = 0; s < kSlots; ++s)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + off[s]),
+                                       (__attribute__((address_space(3))) void*)(S + (wave + s * (NT / 64)) * kPiece),
+                                       16, 0, 0);
+  }
+
+  // registers -> LDS stage S, one float4 slot
+  __device__ __forceinline__ static void store_slot(const floatx4& r, float* S, int tid, int s) {
+    constexpr int LD = BMN + kPad;
+    if constexpr (DIRECT) {  // same place a direct load of this slot writes to
+      const int v = tid + s * NT;
+      *reinterpret_cast<floatx4*>(&S[(v >> 6) * kPiece + (v & 63) * 4]) = r;
+      return;
     }
+    int mn, k;
+    coords(s, tid, mn, k);
+    if (KMAJOR) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) S[(k + e) * LD + mn] = r[e];
+    } else {
+      *reinterpret_cast<floatx4*>(&S[k * LD + mn]) = r;
+    }
+  }
+  __device__ __forceinline__ static void store(const floatx4 (&r)[kSlots], float* S, int tid) {
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) store_slot(r[s], S, tid, s);
   }
 };
 
@@ -264,7 +276,9 @@ constexpr int min_waves_per_simd() {
   return (BM * BN / (WGM * WGN) > 128 * 64) ? 1 : 2;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int WGK, bool TA, bool TB>
+// DLDS: operands whose rows are contiguous in memory (A not transposed, B transposed) go from global memory
+// straight into LDS in the interior loop; the others, and every border tile, take the register path.
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK, bool TA, bool TB, bool DLDS = false, int KMAP = 2>
 __global__ __launch_bounds__(64 * WGM * WGN * WGK, (min_waves_per_simd<BM, BN, WGM, WGN>()))
 void tiled_kernel(TiledParams p) {
   constexpr int NT = 64 * WGM * WGN * WGK;
@@ -274,11 +288,12 @@ void tiled_kernel(TiledParams p) {
   constexpr int FM = WTM / 32, FN = WTN / 32;
   static_assert(FM == 1 || FM == 2 || FM == 4, "wave tile rows must be 32, 64 or 128");
   static_assert(FN == 1 || FN == 2 || FN == 4, "wave tile columns must be 32, 64 or 128");
-  constexpr int LDA_S = BM + kPad, LDB_S = BN + kPad;
-  constexpr int A_STAGE = BK * LDA_S, B_STAGE = BK * LDB_S;
+  static_assert(!DLDS || WGK == 1, "direct-to-LDS loads are built for one wave group");
+  constexpr bool DA = DLDS && !TA, DB = DLDS && TB;
   // A is k-contiguous when transposed; B is k-contiguous when not transposed.
-  using LoadA = OperandLoader<BM, BK, NT, TA>;
-  using LoadB = OperandLoader<BN, BK, NT, !TB>;
+  using LoadA = OperandLoader<BM, BK, NT, TA, DA, KMAP>;
+  using LoadB = OperandLoader<BN, BK, NT, !TB, DB, KMAP>;
+  constexpr int A_STAGE = LoadA::kStage, B_STAGE = LoadB::kStage;
 
   __shared__ __attribute__((aligned(16))) float lds[2 * (A_STAGE + B_STAGE)];
   static_assert((WGK - 1) * BM * BN <= 2 * (A_STAGE + B_STAGE), "the partial sums of the wave groups must fit the stages");
@@ -287,6 +302,7 @@ void tiled_kernel(TiledParams p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // the same number, known to be wave-uniform
   const int h = lane >> 5, pl = lane & 31;
   const int kg = wave / (WGM * WGN), wq = wave % (WGM * WGN);
   const int wm = wq % WGM, wn = wq / WGM;
@@ -326,13 +342,14 @@ void tiled_kernel(TiledParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[c][b][r] = 0.f;
 
-  // Small wave tiles (at most four MFMA blocks) prefetch two K steps ahead through two register
-  // sets per operand: while step t runs on LDS stage t & 1, the tile of step t+1 sits in set
-  // (t+1) & 1 (loaded during step t-1) and the loads of step t+2 go to set t & 1.  Two steps of
-  // matrix work then cover the global-memory latency, which keeps shapes with only one or two
-  // work-groups per CU from being latency-bound.  Large wave tiles have a whole step of 8 x 8+ MFMAs
-  // to hide behind and no registers to spare: one set, one step ahead.
-  constexpr int NS = (FM * FN <= 4) ? 2 : 1;
+  // Wave tiles with little matrix work per K step (at most 32 MFMAs, about 2000 cycles) prefetch two K steps
+  // ahead through two register sets per operand: while step t runs on LDS stage t & 1, the tile of step t+1
+  // sits in set (t+1) & 1 (loaded during step t-1) and the loads of step t+2 go to set t & 1.  Two steps of
+  // matrix work then cover the global-memory latency, which keeps shapes with only one or two work-groups per
+  // CU from being latency-bound.  Larger steps have 4000+ cycles of MFMAs to hide behind and no registers to
+  // spare (a second set pushed some instantiations into spilling inside the interior loop): one set, one
+  // step ahead.
+  constexpr int NS = (FM * FN * (BKW / 2) <= 32 && !DLDS) ? 2 : 1;
   floatx4 ra[NS][LoadA::kSlots], rb[NS][LoadB::kSlots];
 
   auto load_guarded = [&](int ti, floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots])
@@ -353,19 +370,26 @@ void tiled_kernel(TiledParams p) {
   }
   __syncthreads();
 
-  const float* a_rd = As + (kg * BKW + h) * LDA_S + wm * WTM + FM * pl;
-  const float* b_rd = Bs + (kg * BKW + h) * LDB_S + wn * WTN + FN * pl;
+  // row kk + h of a stage sits at row_offset(kk) + row_offset(h) for even kk (a piece holds an even number of
+  // rows, or one); the wave group's first row kg * BKW is even as well
+  const float* a_rd = As + (kg * LoadA::row_offset(BKW) + h * LoadA::row_offset(1)) + wm * WTM + FM * pl;
+  const float* b_rd = Bs + (kg * LoadB::row_offset(BKW) + h * LoadB::row_offset(1)) + wn * WTN + FN * pl;
+  static_assert(WGK == 1 || (!DA && !DB), "row_offset is linear only for the padded-row layout");
 
   // One K step on LDS stage BUF.  Schedule (pinned with scheduling barriers):
   //   - operand registers are double-buffered: the LDS reads of sub-step kk+2 are issued before
   //     the MFMAs of sub-step kk, so their latency hides behind FM*FN matrix instructions;
   //   - the global loads of the step after next are issued once the first block of MFMAs is queued;
-  //   - the LDS stores of the next step (other stage, other register set) are issued in front of
-  //     the last block of MFMAs, so the matrix pipe still has work while the wave writes LDS and
-  //     reaches the barrier.
+  //   - the LDS stores of the next step (other stage, other register set) are spread over the last
+  //     sub-steps, one float4 slot of each operand per sub-step, so that the LDS writes issue in the
+  //     shadow of that sub-step's MFMAs instead of in one clump in front of the barrier.
   // `load_ahead(set_a, set_b)` issues the loads, `have_next` says whether there is anything to store.
-  auto k_step = [&](auto buf_tag, auto&& load_ahead, bool have_next) __attribute__((always_inline)) {
+  // `direct_tag`: this step's load_ahead moves the direct operands into the other stage by itself (interior
+  // loop of a DLDS kernel); their register -> LDS stores are then left out and the loads are awaited before the
+  // barrier, which publishes them to the other waves.
+  auto k_step = [&](auto buf_tag, auto&& load_ahead, bool have_next, auto direct_tag_t) __attribute__((always_inline)) {
     constexpr int BUF = decltype(buf_tag)::value;
+    constexpr bool direct_tag = decltype(direct_tag_t)::value;
     const float* a_s = a_rd + BUF * A_STAGE;
     const float* b_s = b_rd + BUF * B_STAGE;
     float af[2][FM], bf[2][FN];
@@ -375,14 +399,17 @@ void tiled_kernel(TiledParams p) {
     for (int kk = 0; kk < BKW; kk += 2) {
       const int cur = (kk >> 1) & 1;
       if (kk + 2 < BKW) {
-        lds_read_frag<FM>(af[cur ^ 1], a_s + (kk + 2) * LDA_S);
-        lds_read_frag<FN>(bf[cur ^ 1], b_s + (kk + 2) * LDB_S);
+        lds_read_frag<FM>(af[cur ^ 1], a_s + LoadA::row_offset(kk + 2));
+        lds_read_frag<FN>(bf[cur ^ 1], b_s + LoadB::row_offset(kk + 2));
       }
       constexpr int LS = (NS == 2) ? BUF : 0, SS = (NS == 2) ? (BUF ^ 1) : 0;  // load-target / store-source set
-      if (kk == 2) load_ahead(ra[LS], rb[LS]);
-      if (kk == BKW - 2 && have_next) {
-        LoadA::store(ra[SS], As + (BUF ^ 1) * A_STAGE, tid);
-        LoadB::store(rb[SS], Bs + (BUF ^ 1) * B_STAGE, tid);
+      if (kk == 2) load_ahead(ra[LS], rb[LS], As + (BUF ^ 1) * A_STAGE, Bs + (BUF ^ 1) * B_STAGE);
+      if (have_next) {
+        constexpr int NSUB = BKW / 2;
+        static_assert(LoadA::kSlots <= NSUB - 1 && LoadB::kSlots <= NSUB - 1, "one slot per sub-step after the loads");
+        const int sa = (kk >> 1) - (NSUB - LoadA::kSlots), sb = (kk >> 1) - (NSUB - LoadB::kSlots);
+        if (sa >= 0 && !(DA && direct_tag)) LoadA::store_slot(ra[SS][sa], As + (BUF ^ 1) * A_STAGE, tid, sa);
+        if (sb >= 0 && !(DB && direct_tag)) LoadB::store_slot(rb[SS][sb], Bs + (BUF ^ 1) * B_STAGE, tid, sb);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -392,6 +419,7 @@ void tiled_kernel(TiledParams p) {
           acc[c][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(bf[cur][c], af[cur][b], acc[c][b], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    if constexpr (direct_tag && (DA || DB)) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct loads have landed
     __syncthreads();
   };
   using Buf0 = std::integral_constant<int, 0>;
@@ -411,15 +439,21 @@ void tiled_kernel(TiledParams p) {
     const int64_t sa = LoadA::fast_stride(p.lda), sb = LoadB::fast_stride(p.ldb);
     auto interior = [&](auto aligned_tag) __attribute__((always_inline)) {
       constexpr bool AL = decltype(aligned_tag)::value;
-      auto lean = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots]) __attribute__((always_inline)) {
-        LoadA::template fast_load<AL>(qa, pa, offa);
-        LoadB::template fast_load<AL>(qb, pb, offb);
+      // operands that go straight to LDS need 16-byte aligned addresses; without them the kernel still works,
+      // through the register path
+      constexpr bool DIRECT_NOW = AL && (DA || DB);
+      auto lean = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots], float* sa_next, float* sb_next)
+                      __attribute__((always_inline)) {
+        if constexpr (DIRECT_NOW && DA) LoadA::direct_load(pa, offa, sa_next, wave_u);
+        else LoadA::template fast_load<AL>(qa, pa, offa);
+        if constexpr (DIRECT_NOW && DB) LoadB::direct_load(pb, offb, sb_next, wave_u);
+        else LoadB::template fast_load<AL>(qb, pb, offb);
         pa += sa;
         pb += sb;
       };
       for (; t + NS + 1 < n_full; t += 2) {  // loads tiles t+NS and t+NS+1, both full
-        k_step(Buf0{}, lean, true);
-        k_step(Buf1{}, lean, true);
+        k_step(Buf0{}, lean, true, std::integral_constant<bool, DIRECT_NOW>{});
+        k_step(Buf1{}, lean, true, std::integral_constant<bool, DIRECT_NOW>{});
       }
     };
     if (a_al && b_al) interior(std::true_type{});
@@ -427,11 +461,10 @@ void tiled_kernel(TiledParams p) {
   }
   // ---- everything else (edge tiles, unaligned operands, the K tail): guarded loads
   for (; t < n_steps; ++t) {
-    auto guarded = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots]) __attribute__((always_inline)) {
-      load_guarded(t + NS, qa, qb);
-    };
-    if (t & 1) k_step(Buf1{}, guarded, t + 1 < n_steps);
-    else k_step(Buf0{}, guarded, t + 1 < n_steps);
+    auto guarded = [&](floatx4 (&qa)[LoadA::kSlots], floatx4 (&qb)[LoadB::kSlots], float*, float*)
+                       __attribute__((always_inline)) { load_guarded(t + NS, qa, qb); };
+    if (t & 1) k_step(Buf1{}, guarded, t + 1 < n_steps, std::false_type{});
+    else k_step(Buf0{}, guarded, t + 1 < n_steps, std::false_type{});
   }
 
   // ---- partial sums of wave groups 1 .. WGK-1 go through LDS (the stages are free after the last
@@ -533,7 +566,7 @@ void tiled_kernel(TiledParams p) {
   }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int WGK>
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK, bool DLDS, int KMAP>
 static int launch_cfg(int split_k, const GemmArgs& g, int64_t a_rows, int64_t b_cols) {
   TiledParams p;
   p.A = g.A, p.B = g.B, p.C = g.C, p.ws = g.ws;
@@ -551,11 +584,11 @@ static int launch_cfg(int split_k, const GemmArgs& g, int64_t a_rows, int64_t b_
   p.b_vec = ((g.ldb & 3) == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0);
   dim3 grid((unsigned)(tiles_m * tiles_n * split_k)), block(64 * WGM * WGN * WGK);
   if (g.tA) {
-    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, true><<<grid, block, 0, stream_of(g)>>>(p);
-    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, false><<<grid, block, 0, stream_of(g)>>>(p);
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, true, DLDS, KMAP><<<grid, block, 0, stream_of(g)>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, true, false, DLDS, KMAP><<<grid, block, 0, stream_of(g)>>>(p);
   } else {
-    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, true><<<grid, block, 0, stream_of(g)>>>(p);
-    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, false><<<grid, block, 0, stream_of(g)>>>(p);
+    if (g.tB) tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, true, DLDS, KMAP><<<grid, block, 0, stream_of(g)>>>(p);
+    else tiled_kernel<BM, BN, BK, WGM, WGN, WGK, false, false, DLDS, KMAP><<<grid, block, 0, stream_of(g)>>>(p);
   }
   int st = check_launch();
   if (st != MDG_OK || split_k == 1) return st;
@@ -564,9 +597,9 @@ static int launch_cfg(int split_k, const GemmArgs& g, int64_t a_rows, int64_t b_
 
 int launch_tiled(int cfg, int split_k, const GemmArgs& g, int64_t a_rows, int64_t b_cols) {
   switch (cfg) {
-#define X(c, BM, BN, BK, WGM, WGN, WGK) \
-  case c:                               \
-    return launch_cfg<BM, BN, BK, WGM, WGN, WGK>(split_k, g, a_rows, b_cols);
+#define X(c, BM, BN, BK, WGM, WGN, WGK, DLDS, KMAP) \
+  case c:                                           \
+    return launch_cfg<BM, BN, BK, WGM, WGN, WGK, (DLDS) != 0, KMAP>(split_k, g, a_rows, b_cols);
     MDG_TILED_CONFIGS(X)
 #undef X
   }

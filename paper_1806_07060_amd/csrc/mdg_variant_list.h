@@ -20,29 +20,39 @@
   X(6, 1, 4, 0)
 
 // Tiled matrix-core kernel: work-group tile BM x BN x BK, WGM x WGN waves per wave group, WGK wave
-// groups that split every K step among themselves (partial sums added through LDS).
-//   X(cfg, BM, BN, BK, WGM, WGN, WGK)
+// groups that split every K step among themselves (partial sums added through LDS).  DLDS = 1: operands
+// whose rows are contiguous in memory are loaded from global memory straight into LDS in the interior loop
+// (legal only when those operands are 16-byte aligned).
+// KMAP = lane arrangement of the global loads of k-contiguous operands (0, 1 or 2, see the kernel).
+//   X(cfg, BM, BN, BK, WGM, WGN, WGK, DLDS, KMAP)
 #define MDG_TILED_CONFIGS(X)       \
-  X(0, 256, 256, 16, 2, 4, 1)      \
-  X(1, 256, 128, 16, 2, 2, 1)      \
-  X(2, 128, 256, 16, 2, 2, 1)      \
-  X(3, 128, 128, 16, 2, 2, 1)      \
-  X(4, 128, 128, 32, 2, 2, 1)      \
-  X(5, 128, 64, 16, 2, 2, 1)       \
-  X(6, 64, 128, 16, 2, 2, 1)       \
-  X(7, 64, 64, 16, 2, 2, 1)        \
-  X(8, 64, 64, 32, 2, 2, 1)        \
-  X(9, 32, 32, 32, 1, 1, 1)        \
-  X(10, 256, 256, 32, 2, 4, 1)     \
-  X(11, 128, 32, 32, 4, 1, 1)      \
-  X(12, 32, 128, 32, 1, 4, 1)      \
-  X(13, 32, 32, 64, 1, 1, 4)       \
-  X(14, 32, 32, 128, 1, 1, 8)      \
-  X(15, 64, 64, 64, 2, 2, 4)       \
-  X(16, 64, 64, 32, 2, 2, 2)       \
-  X(17, 128, 128, 32, 2, 2, 2)     \
-  X(18, 64, 32, 32, 2, 1, 1)       \
-  X(19, 32, 64, 32, 1, 2, 1)
+  X(0, 256, 256, 16, 2, 4, 1, 0, 2)      \
+  X(1, 256, 128, 16, 2, 2, 1, 0, 2)      \
+  X(2, 128, 256, 16, 2, 2, 1, 0, 2)      \
+  X(3, 128, 128, 16, 2, 2, 1, 0, 2)      \
+  X(4, 128, 128, 32, 2, 2, 1, 0, 2)      \
+  X(5, 128, 64, 16, 2, 2, 1, 0, 2)       \
+  X(6, 64, 128, 16, 2, 2, 1, 0, 2)       \
+  X(7, 64, 64, 16, 2, 2, 1, 0, 2)        \
+  X(8, 64, 64, 32, 2, 2, 1, 0, 2)        \
+  X(9, 32, 32, 32, 1, 1, 1, 0, 2)        \
+  X(10, 256, 256, 32, 2, 4, 1, 0, 2)     \
+  X(11, 128, 32, 32, 4, 1, 1, 0, 2)      \
+  X(12, 32, 128, 32, 1, 4, 1, 0, 2)      \
+  X(13, 32, 32, 64, 1, 1, 4, 0, 2)       \
+  X(14, 32, 32, 128, 1, 1, 8, 0, 2)      \
+  X(15, 64, 64, 64, 2, 2, 4, 0, 2)       \
+  X(16, 64, 64, 32, 2, 2, 2, 0, 2)       \
+  X(17, 128, 128, 32, 2, 2, 2, 0, 2)     \
+  X(18, 64, 32, 32, 2, 1, 1, 0, 2)       \
+  X(19, 32, 64, 32, 1, 2, 1, 0, 2)       \
+  X(20, 64, 32, 32, 2, 1, 2, 0, 2)       \
+  X(21, 32, 64, 32, 1, 2, 2, 0, 2)       \
+  X(22, 128, 64, 32, 2, 2, 1, 0, 2)      \
+  X(23, 64, 128, 32, 2, 2, 1, 0, 2)        \
+  X(24, 128, 128, 32, 2, 2, 1, 1, 2)       \
+  X(25, 128, 256, 16, 2, 2, 1, 1, 2)       \
+  X(26, 256, 128, 16, 2, 2, 1, 1, 2)
 
 // Skinny-N kernels: stream A once; NB columns of C per pass over A.
 //   X(cfg, NB, MATRIX)   MATRIX = 0: vector-ALU kernels, NB columns held per thread
@@ -136,4 +146,11 @@
   V(INDIRECT, 0, 1)     \
   V(INDIRECT, 1, 1)     \
   V(INDIRECT, 2, 1)     \
-  V(INDIRECT, 3, 1)
+  V(INDIRECT, 3, 1)  \
+  V(TILED, 20, 1)       \
+  V(TILED, 21, 1)       \
+  V(TILED, 22, 1)       \
+  V(TILED, 23, 1)  \
+  V(TILED, 24, 1)       \
+  V(TILED, 25, 1)       \
+  V(TILED, 26, 1)

@@ -279,3 +279,34 @@ def test_indirect_variants_pack_pad_and_match_the_oracle(tA, tB):
     finally:
         ws = gu._WS["t"]
         assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0
+
+
+@pytest.mark.parametrize("tA,tB", TT)
+def test_interior_loop_of_every_tiled_and_indirect_variant_is_exact(tA, tB):
+    # aligned operands with whole tiles and a long K: the lean interior loop (vector loads, direct-to-LDS loads,
+    # every lane arrangement) does all the work; integer data, so the oracle's bits are the only right answer.
+    # A second case breaks the alignment (leading dimensions + 1), which direct-to-LDS variants must refuse.
+    gu = _gu()
+    base = GemmCase(512, 768, 416, tA, tB, 1.0, 0.5, dist="smallint", c0="smallint", seed=wl.case_seed(17, 2 * tA + tB),
+                    name=f"interior/{tA}{tB}").resolved()
+    odd = GemmCase(**{**base.__dict__, "lda": base.lda + 1, "ldb": base.ldb + 1, "name": base.name + "/odd-ld"})
+    n_direct = 0
+    for case in (base, odd):
+        A, B, C0 = wl.make_operands(case)
+        ref = gu.oracle_result(case, A, B, C0)
+        legal = gu.legal_variants(case)
+        for d in mdg.variants():
+            if d["family"] not in (mdg.FAMILY_TILED, mdg.FAMILY_INDIRECT) or d["split_k"] > 4:
+                continue
+            if d["lds"] == 2 and case is odd and (tA == NT or tB == TR):
+                assert d["id"] not in legal, d["name"]  # an unaligned row-contiguous operand: not for direct loads
+                continue
+            assert d["id"] in legal, d["name"]
+            n_direct += d["lds"] == 2
+            st, got, *_ = gu.run_case(case, variant=d["id"])
+            assert st == 0, (d["name"], mdg.mdg_status_string(st))
+            try:
+                gu.check_against_oracle(case, got, A, B, C0, exact=True, ref=ref)
+            except AssertionError as e:
+                raise AssertionError(f"{d['name']}: {e}") from None
+    assert n_direct >= 2

@@ -54,6 +54,9 @@ def test_fallback_chains_end_at_variant_zero_and_only_relax_the_variant():
             if x["family"] == mdg.FAMILY_TILED and x["split_k"] > 1:  # fewer K slices of the same tile
                 assert nxt["family"] == x["family"] and nxt["split_k"] < x["split_k"]
                 assert (nxt["tile_m"], nxt["tile_n"], nxt["tile_k"]) == (x["tile_m"], x["tile_n"], x["tile_k"])
+            elif x["family"] == mdg.FAMILY_TILED and x["lds"] == 2:  # the same tile with loads through registers
+                assert nxt["family"] == mdg.FAMILY_TILED and nxt["split_k"] == 1 and nxt["lds"] == 1
+                assert (nxt["tile_m"], nxt["tile_n"], nxt["tile_k"], nxt["threads"]) == (x["tile_m"], x["tile_n"], x["tile_k"], x["threads"])
             elif x["family"] == mdg.FAMILY_INDIRECT:  # the same tile without the helper passes
                 assert nxt["family"] == mdg.FAMILY_TILED and nxt["split_k"] == 1
                 assert (nxt["tile_m"], nxt["tile_n"], nxt["tile_k"]) == (x["tile_m"], x["tile_n"], x["tile_k"])
@@ -208,6 +211,22 @@ def test_workspace_registration_errors_have_their_own_code():
     assert mdg.mdg_variant_legal(sk, 0, 0, 128, 128, 4096, 128, 4096, 128) == 1
     assert mdg.mdg_set_workspace(0, 0) == 0
     assert mdg.mdg_variant_legal(sk, 0, 0, 128, 128, 4096, 128, 4096, 128) == 0
+
+
+def test_direct_to_lds_variants_demand_aligned_row_contiguous_operands():
+    vs = [v for v in mdg.variants() if v["family"] == mdg.FAMILY_TILED and v["lds"] == 2]
+    assert len(vs) >= 2
+    for v in vs:
+        i = v["id"]
+        # A not transposed: lda and the pointer must keep 16-byte alignment; a transposed A goes through registers
+        assert mdg.mdg_variant_legal(i, 0, 0, 512, 512, 512, 512, 512, 512, 4096, 4096, 4096) == 1
+        assert mdg.mdg_variant_legal(i, 0, 0, 512, 512, 512, 513, 512, 512, 4096, 4096, 4096) == 0
+        assert mdg.mdg_variant_legal(i, 0, 0, 512, 512, 512, 512, 512, 512, 4100, 4096, 4096) == 0
+        assert mdg.mdg_variant_legal(i, 1, 0, 512, 512, 512, 513, 513, 512, 4100, 4100, 4096) == 1
+        # B transposed: the same for ldb and B
+        assert mdg.mdg_variant_legal(i, 1, 1, 512, 512, 512, 513, 512, 512, 4100, 4096, 4096) == 1
+        assert mdg.mdg_variant_legal(i, 1, 1, 512, 512, 512, 512, 514, 512, 4096, 4096, 4096) == 0
+        assert mdg.mdg_variant_legal(i, 1, 1, 512, 512, 512, 512, 512, 512, 4096, 4104, 4096) == 0
 
 
 def test_indirect_variants_need_workspace_for_the_packed_copies_only():
