@@ -52,7 +52,9 @@
   X(23, 64, 128, 32, 2, 2, 1, 0, 2)        \
   X(24, 128, 128, 32, 2, 2, 1, 1, 2)       \
   X(25, 128, 256, 16, 2, 2, 1, 1, 2)       \
-  X(26, 256, 128, 16, 2, 2, 1, 1, 2)
+  X(26, 256, 128, 16, 2, 2, 1, 1, 2)    \
+  X(27, 32, 32, 256, 1, 1, 4, 0, 2)     \
+  X(28, 64, 64, 128, 2, 2, 4, 0, 2)
 
 // Skinny-N kernels: stream A once; NB columns of C per pass over A.
 //   X(cfg, NB, MATRIX)   MATRIX = 0: vector-ALU kernels, NB columns held per thread
@@ -153,4 +155,6 @@
   V(TILED, 23, 1)  \
   V(TILED, 24, 1)       \
   V(TILED, 25, 1)       \
-  V(TILED, 26, 1)
+  V(TILED, 26, 1)  \
+  V(TILED, 27, 1)       \
+  V(TILED, 28, 1)

@@ -111,6 +111,43 @@ def measure_case(case, pools, stream, variants, span_ms=1.0, spans=3, prune=6.0,
     return out
 
 
+def verify_case(case, pools, stream, variants):
+    """Run every legal variant once on the first operand set of the pools and hold its C to variant 0's (the
+    universal direct kernel, itself held to the oracle by the tests): |C_v - C_0| <= 2e-6 K max|a| max|b| +
+    2e-6 |beta C0| (two results that each meet the library's tolerance differ by at most twice that).  Returns
+    (pairs checked, worst error / bound).  A timing of a kernel that computes the wrong thing is worthless; this
+    is the tuning run's own guard, not a parity test."""
+    torch = pools.torch
+    c = case.resolved()
+    na = wl.buffer_len(c.layout, c.a_shape(), c.lda)
+    nb = wl.buffer_len(c.layout, c.b_shape(), c.ldb)
+    nc = wl.buffer_len(c.layout, c.c_shape(), c.ldc)
+    C0 = pools.C[:nc].clone()
+
+    def run(v):
+        out = C0.clone()
+        st = mdg.mdg_sgemm_variant(v, c.layout, c.transA, c.transB, c.M, c.N, c.K, c.alpha, pools.A.data_ptr(), c.lda,
+                                   pools.B.data_ptr(), c.ldb, c.beta, out.data_ptr(), c.ldc, stream)
+        if st != 0:
+            raise RuntimeError(f"variant {v} on {c.name}: {mdg.mdg_status_string(st)}")
+        return out
+
+    ref = run(0)
+    bound = 2e-6 * c.K * float(pools.A[:na].abs().max()) * float(pools.B[:nb].abs().max()) + 2e-6 * abs(c.beta) * C0.abs()
+    bound = torch.clamp(bound, min=1e-30)
+    worst, n = 0.0, 0
+    for v in range(1, len(variants)):
+        if mdg.mdg_variant_legal(v, c.tA(), c.tB(), c.M, c.N, c.K, c.lda, c.ldb, c.ldc, pools.A.data_ptr(),
+                                 pools.B.data_ptr(), C0.data_ptr()) != 1:
+            continue
+        ratio = float(((run(v) - ref).abs() / bound).max()) if nc else 0.0
+        if not ratio <= 1.0:
+            raise RuntimeError(f"{variants[v]['name']} on {c.name} ({c.M}x{c.N}x{c.K}, tA={c.tA()}, tB={c.tB()}): result "
+                               f"differs from variant 0 by {ratio:.2f} x the bound")
+        worst, n = max(worst, ratio), n + 1
+    return n, worst
+
+
 def recheck_case(case, pools, stream, variants, times, span_ms=1.0, spans=3, prune=6.0, max_reps=200, below=1e-3):
     """Second look at entries that were recorded from one probe call (slower than prune x the row's best) and are
     short enough (< `below` seconds) for a cold first launch to have distorted them: probe again, and measure
@@ -182,13 +219,16 @@ def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, default=4,
                     help="0-4: the five workload configurations; 5: go2 grid; 6: po2 grid; 7: wide random sweep; 8: large products; 9: coarse grid of the largest sizes; 10: thin (few columns); 11: flat (few rows); 12 / 13: geometric grids over the thin / flat corners")
-    ap.add_argument("--out", required=True)
+    ap.add_argument("--out", default=None, help="the table to write (required unless --verify-every)")
     ap.add_argument("--start", type=int, default=0)
     ap.add_argument("--limit", type=int, default=10 ** 9)
     ap.add_argument("--budget-s", type=float, default=1e9, help="stop cleanly after this many seconds")
     ap.add_argument("--span-ms", type=float, default=1.0)
     ap.add_argument("--spans", type=int, default=3)
     ap.add_argument("--prune", type=float, default=6.0)
+    ap.add_argument("--verify-every", type=int, default=0, metavar="N",
+                    help="instead of timing: for every N-th input run every legal variant once and hold its result "
+                         "to variant 0's (see verify_case); prints a summary, writes no table")
     ap.add_argument("--recheck-from", default=None, metavar="CSV",
                     help="a finished table of the same inputs and variants: re-measure only the short entries that "
                          "were recorded from a single probe call, write the corrected table to --out")
@@ -200,6 +240,8 @@ def main(argv=None):
                          "already holds (matched by name) are copied, only the new variants are measured")
     args = ap.parse_args(argv)
 
+    if args.out is None and args.verify_every <= 0:
+        ap.error("--out is required")
     import torch
     assert torch.cuda.is_available(), "the tuning run needs a GPU"
     mdg.lib()
@@ -210,6 +252,20 @@ def main(argv=None):
     assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0
     stream = torch.cuda.current_stream().cuda_stream
 
+    if args.verify_every > 0:
+        t0, pairs, worst, shapes = time.time(), 0, 0.0, 0
+        for i, c in enumerate(cases):
+            if i % args.verify_every or i < args.start or i >= args.start + args.limit:
+                continue
+            n, w = verify_case(c, pools, stream, variants)
+            pairs, worst, shapes = pairs + n, max(worst, w), shapes + 1
+            if shapes % 20 == 0:
+                print(f"[{time.time() - t0:7.1f}s] {shapes} inputs, {pairs} (input, variant) results verified, worst "
+                      f"error / bound {worst:.3f}", flush=True)
+        mdg.mdg_set_workspace(0, 0)
+        print(f"verified: {shapes} inputs of config {args.config}, {pairs} (input, variant) results against variant 0, "
+              f"worst error / bound {worst:.3f}, {time.time() - t0:.1f}s", flush=True)
+        return
     os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
     header, done = load_done(args.out)
     want_header = ["index", "name", "M", "N", "K", "tA", "tB", "alpha", "beta"] + [v["name"] for v in variants]
