@@ -325,14 +325,21 @@ void tiled_kernel(TiledParams p) {
   const int in_group = bid - group * group_sz;
   const int tile_m = first_m + in_group % gm;
   const int tile_n = in_group / gm;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  // The tile stores rows [ms, ms + BM) and columns [ns, ns + BN) of C.  A border tile of a matrix that is at
+  // least one tile tall (wide) is moved back so that it ends exactly at the edge: it then loads whole tiles like
+  // an interior one (no guarded loads along the whole K range, which cost a large tile most of its speed); the
+  // rows (columns) below ms (ns) it computes on the way belong to its neighbour and are not stored.
+  const int ms = tile_m * BM, ns = tile_n * BN;
+  const int m0 = (ms + BM > p.Ma && p.Ma >= BM) ? p.Ma - BM : ms;
+  const int n0 = (ns + BN > p.Nb && p.Nb >= BN) ? p.Nb - BN : ns;
 
   const int k_begin = split * p.k_per_split;
   const int k_end = min(p.K, k_begin + p.k_per_split);
   const int n_steps = (k_end - k_begin + BK - 1) / BK;
 
   const bool a_full = (m0 + BM <= p.Ma), b_full = (n0 + BN <= p.Nb);  // tile inside the operand along m / n
-  const bool a_al = p.a_vec != 0, b_al = p.b_vec != 0;              // 16-byte loads of that operand are aligned
+  // 16-byte loads of that operand are aligned (a moved tile of a row-contiguous operand may start off the grid)
+  const bool a_al = p.a_vec != 0 && (TA || (m0 & 3) == 0), b_al = p.b_vec != 0 && (!TB || (n0 & 3) == 0);
 
   floatx16 acc[FN][FM];
 #pragma unroll
@@ -500,14 +507,14 @@ void tiled_kernel(TiledParams p) {
   if (p.split_k > 1) {
     // raw partial sums into slice `split` of the workspace (tight column-major M x N)
     float* W = p.ws + (int64_t)split * p.M * p.N;
-    const bool vec = (FM > 1) && (m_base + FM <= p.M);  // the lane's FM rows are all inside
-    const bool w_al = (p.M & 3) == 0;                    // slices are 256-byte aligned, columns M floats apart
+    const bool vec = (FM > 1) && (m_base >= ms) && (m_base + FM <= p.M);  // the lane's FM rows are all this tile's
+    const bool w_al = ((p.M | m0) & 3) == 0;             // slices are 256-byte aligned, columns M floats apart
 #pragma unroll
     for (int c = 0; c < FN; ++c)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
-        if (n >= p.N) continue;
+        if (n < ns || n >= p.N) continue;
         float* dst = W + (int64_t)m_base + (int64_t)n * p.M;
         if (vec) {
           float o[FM];
@@ -517,14 +524,14 @@ void tiled_kernel(TiledParams p) {
         } else {
 #pragma unroll
           for (int b = 0; b < FM; ++b)
-            if (m_base + b < p.M) dst[b] = acc[c][b][r];
+            if (m_base + b >= ms && m_base + b < p.M) dst[b] = acc[c][b][r];
         }
       }
     return;
   }
 
-  const bool c_al = ((p.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
-  const bool vec = (FM > 1) && (m_base + FM <= p.M);  // the lane's FM rows are all inside
+  const bool c_al = (((p.ldc | m0) & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0);
+  const bool vec = (FM > 1) && (m_base >= ms) && (m_base + FM <= p.M);  // the lane's FM rows are all this tile's
   const float alpha = p.alpha, beta = p.beta;
   // Per block column c: first all reads of the old C (16 independent loads in flight per lane --
   // read-then-write one row at a time would pay the memory latency sixteen times), then scale and store.
@@ -547,7 +554,7 @@ void tiled_kernel(TiledParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int n = n_wave + FN * (8 * (r >> 2) + 4 * h + (r & 3)) + c;
-      if (n >= p.N) continue;
+      if (n < ns || n >= p.N) continue;
       float* dst = p.C + (int64_t)m_base + (int64_t)n * p.ldc;
       float o[FM];
 #pragma unroll
@@ -560,7 +567,7 @@ void tiled_kernel(TiledParams p) {
       } else {
 #pragma unroll
         for (int b = 0; b < FM; ++b)
-          if (m_base + b < p.M) dst[b] = o[b];
+          if (m_base + b >= ms && m_base + b < p.M) dst[b] = o[b];
       }
     }
   }

@@ -19,6 +19,8 @@ def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--variants", required=True, help="comma-separated variant names (mdg_variant_info().name)")
     ap.add_argument("--sizes", default="8192,4096")
+    ap.add_argument("--shapes", default="", help="further cases MxNxK[,MxNxK...] (tight leading dimensions, all four "
+                                                 "transpose combinations, alpha = 1, beta = 0.5)")
     ap.add_argument("--rounds", type=int, default=3)
     args = ap.parse_args(argv)
     import torch
@@ -30,9 +32,15 @@ def main(argv=None):
     ws = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
     assert mdg.mdg_set_workspace(ws.data_ptr(), ws.numel() * 4) == 0
     stream = torch.cuda.current_stream().cuda_stream
-    for n in (int(x) for x in args.sizes.split(",")):
-        for case in wl.config1(sizes=(n,)):
+    cases = [c for n in (int(x) for x in args.sizes.split(",") if x) for c in wl.config1(sizes=(n,))]
+    for spec in (x for x in args.shapes.split(",") if x):
+        M, N, K = (int(v) for v in spec.split("x"))
+        cases += [wl.GemmCase(M, N, K, ta, tb, 1.0, 0.5, name=f"{spec}/{'NT'[ta != wl.NO_TRANS]}{'NT'[tb != wl.NO_TRANS]}")
+                  for ta in (wl.NO_TRANS, wl.TRANS) for tb in (wl.NO_TRANS, wl.TRANS)]
+    for case in cases:
+        if True:
             c = case.resolved()
+            n = max(c.M, c.N, c.K)
             n_sets, sa, sb, sc = pools.layout(c)
             best = {}
             for _ in range(args.rounds):
