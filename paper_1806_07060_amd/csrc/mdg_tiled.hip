@@ -202,11 +202,16 @@ struct OperandLoader {
   __device__ __forceinline__ static bool offsets_fit(int64_t ld) {
     return (KMAJOR ? (int64_t)BMN : (int64_t)BK) * ld * 4 < 0x7fffffffLL;
   }
-  __device__ __forceinline__ static void fast_offsets(uint32_t (&off)[kSlots], int64_t ld, int tid) {
+  // `rows` < BMN: the operand ends inside the tile.  Slots past its end re-read its last row (its last four
+  // rows when rows are contiguous along mn; `rows` must then be a multiple of four): what they bring in only
+  // reaches elements of C that are never stored, and it is finite whenever the operand is.
+  __device__ __forceinline__ static bool rows_clampable(int rows) { return KMAJOR || ((rows & 3) == 0 && rows >= 4); }
+  __device__ __forceinline__ static void fast_offsets(uint32_t (&off)[kSlots], int64_t ld, int tid, int rows) {
 #pragma unroll
     for (int s = 0; s < kSlots; ++s) {
       int mn, k;
       coords(s, tid, mn, k);
+      mn = min(mn, rows - (KMAJOR ? 1 : 4));
       off[s] = (uint32_t)(4 * (KMAJOR ? (int64_t)k + (int64_t)mn * ld : (int64_t)mn + (int64_t)k * ld));
     }
   }
@@ -435,12 +440,15 @@ void tiled_kernel(TiledParams p) {
   int t = 0;
   // ---- interior tiles: K steps whose second successor is a full tile use the lean loads (one instance of the
   // loop for aligned operands, one that goes through the 4-byte-aligned vector type for everything else)
-  const int n_full = (a_full && b_full && LoadA::offsets_fit(p.lda) && LoadB::offsets_fit(p.ldb))
+  // An operand with fewer rows than the tile takes them too when the missing rows can be stood in for.
+  const int rows_a = min(BM, p.Ma - m0), rows_b = min(BN, p.Nb - n0);
+  const int n_full = (LoadA::rows_clampable(rows_a) && LoadB::rows_clampable(rows_b) && LoadA::offsets_fit(p.lda) &&
+                      LoadB::offsets_fit(p.ldb))
                          ? (k_end - k_begin) / BK : 0;
   if (n_full > NS + 1) {
     uint32_t offa[LoadA::kSlots], offb[LoadB::kSlots];
-    LoadA::fast_offsets(offa, p.lda, tid);
-    LoadB::fast_offsets(offb, p.ldb, tid);
+    LoadA::fast_offsets(offa, p.lda, tid, rows_a);
+    LoadB::fast_offsets(offb, p.ldb, tid, rows_b);
     const char* pa = LoadA::fast_base(p.A, p.lda, m0, k_begin + NS * BK);
     const char* pb = LoadB::fast_base(p.B, p.ldb, n0, k_begin + NS * BK);
     const int64_t sa = LoadA::fast_stride(p.lda), sb = LoadB::fast_stride(p.ldb);

@@ -4,7 +4,7 @@
 
 For every square case of the given sizes (all four transpose combinations, alpha = 1, beta = 0.5) each listed
 variant that is legal is timed with the library's event core on rotating operand sets, `--rounds` times in turn;
-the best round is printed as TFLOP/s.  Differences between boxes and between runs are 1-2 %, larger than many
+the best round is printed as TFLOP/s and as microseconds per call.  Differences between boxes and between runs are 1-2 %, larger than many
 kernel effects, so design choices inside a kernel family (lane arrangements, direct-to-LDS loads, tile shapes)
 are compared here rather than across runs of the benchmark.
 """
@@ -51,7 +51,7 @@ def main(argv=None):
                     reps = 6 if n >= 8192 else 20 if n >= 2048 else 100
                     t = harness.time_variant(i, c, pools, n_sets, sa, sb, sc, stream, 2, reps, 3)
                     best[i] = min(best.get(i, t), t)
-            print(c.name, " | ".join(f"{table[i]['name']} {c.flops() / t / 1e12:.1f}" for i, t in best.items()), flush=True)
+            print(c.name, " | ".join(f"{table[i]['name']} {c.flops() / t / 1e12:.1f} ({t * 1e6:.1f} us)" for i, t in best.items()), flush=True)
     mdg.mdg_set_workspace(0, 0)
 
 

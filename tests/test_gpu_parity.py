@@ -310,3 +310,28 @@ def test_interior_loop_of_every_tiled_and_indirect_variant_is_exact(tA, tB):
             except AssertionError as e:
                 raise AssertionError(f"{d['name']}: {e}") from None
     assert n_direct >= 2
+
+
+@pytest.mark.parametrize("tA,tB", TT)
+def test_operands_shorter_than_the_tile_are_exact(tA, tB):
+    # M and N below every large tile with a long K: tiles whose operand ends inside them stand in its last rows
+    # for the missing ones in the interior loop (a multiple of four rows, or k-contiguous rows) and take guarded
+    # loads otherwise (M = 30); what the stand-ins produce must never reach C.  Every legal variant, split-K
+    # included, with beta != 0 and integer data: the oracle's bits are the only right answer.
+    gu = _gu()
+    for M, N, K in ((100, 20, 1312), (30, 52, 1312), (20, 7, 2560)):
+        case = GemmCase(M, N, K, tA, tB, 1.0, 0.5, dist="smallint", c0="smallint",
+                        seed=wl.case_seed(18, 2 * tA + tB), name=f"short/{M}x{N}x{K}/{tA}{tB}").resolved()
+        A, B, C0 = wl.make_operands(case)
+        ref = gu.oracle_result(case, A, B, C0)
+        n_split = 0
+        for v in gu.legal_variants(case):
+            d = mdg.variants()[v]
+            st, got, *_ = gu.run_case(case, variant=v)
+            assert st == 0, (d["name"], mdg.mdg_status_string(st))
+            n_split += d["split_k"] > 1
+            try:
+                gu.check_against_oracle(case, got, A, B, C0, exact=True, ref=ref)
+            except AssertionError as e:
+                raise AssertionError(f"{d['name']}: {e}") from None
+        assert n_split >= 10
