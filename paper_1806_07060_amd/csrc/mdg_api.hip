@@ -1,6 +1,6 @@
 // C-ABI entry points that enqueue GPU work: the GEMM call, the forced-variant call and the event-timing core of
 // the tuning run.  Validation, selection and legality are host code in mdg_dispatch.cpp; the kernels live in
-// mdg_direct.hip, mdg_tiled.hip and mdg_skinny.hip.
+// mdg_direct.hip, mdg_tiled.hip, mdg_skinny.hip and mdg_indirect.hip.
 #include <atomic>
 #include <mutex>
 
