@@ -186,7 +186,7 @@ def config3():
     return cases
 
 
-def config4(n_shapes=2000, max_flops=2 ** 32, seed=None):
+def config4(n_shapes=2000, max_flops=2 ** 32, seed=None, config_index=4, prefix="cfg4"):
     """Random sweep for selector training and evaluation.
 
     M, N, K = round(2**(13 u)), u ~ U[0,1], drawn independently; the whole
@@ -195,7 +195,7 @@ def config4(n_shapes=2000, max_flops=2 ** 32, seed=None):
     is 0, 1 or U[-1, 1] with probability 1/3 each.  Returns the cases in the
     shuffled order used for the 80/20 split (`split_train_heldout`).
     """
-    rng = np.random.Generator(np.random.PCG64(case_seed(4, 0) if seed is None else seed))
+    rng = np.random.Generator(np.random.PCG64(case_seed(config_index, 0) if seed is None else seed))
     cases = []
     while len(cases) < n_shapes:
         dims = [int(round(2.0 ** (13.0 * rng.uniform()))) for _ in range(3)]
@@ -210,9 +210,15 @@ def config4(n_shapes=2000, max_flops=2 ** 32, seed=None):
         beta = (0.0, 1.0, beta_draw)[which]
         i = len(cases)
         cases.append(GemmCase(dims[0], dims[1], dims[2], ta, tb, alpha, beta, dist="uniform",
-                              c0="uniform", seed=case_seed(4, i + 1), name=f"cfg4/{i}"))
+                              c0="uniform", seed=case_seed(config_index, i + 1), name=f"{prefix}/{i}"))
     order = rng.permutation(n_shapes)
     return [cases[i] for i in order]
+
+
+def config_sweep2(n_shapes=4000):
+    """A second random sweep drawn exactly like config4 from a stream of its own.  All of it trains (minus any
+    shape that also occurs in an evaluation set): more inputs from the distribution the held-out shapes come from."""
+    return config4(n_shapes, config_index=14, prefix="sweep2")
 
 
 def fresh_shapes(n_shapes, seed_index=0, log2_max_dim=13.0, max_flops=2 ** 32, min_work=0):
@@ -330,6 +336,16 @@ def config_flat(n_shapes=1200):
     """Flat products (few rows, very many columns): M in [16, 512], N in [1024, 65536], K in [16, 4096],
     each log-uniform.  The region of convolutions lowered to GEMM."""
     return _log_uniform_sweep(11, "flat", n_shapes, (16, 512), (1024, 65536), (16, 4096))
+
+
+def config_thin2(n_shapes=2000):
+    """More of the thin corner, drawn like config_thin from a stream of its own."""
+    return _log_uniform_sweep(15, "thin2", n_shapes, (256, 16384), (1, 64), (256, 8192))
+
+
+def config_flat2(n_shapes=2000):
+    """More of the flat corner, drawn like config_flat from a stream of its own."""
+    return _log_uniform_sweep(16, "flat2", n_shapes, (16, 512), (1024, 65536), (16, 4096))
 
 
 def _geometric_grid(lo, hi):

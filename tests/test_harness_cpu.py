@@ -104,3 +104,19 @@ def test_training_set_generators_are_seeded_capped_and_cover_their_corners():
     assert [(c.M, c.N, c.K, c.transA, c.transB, c.alpha, c.beta) for c in wl.config_flat_grid()] == \
         [(c.M, c.N, c.K, c.transA, c.transB, c.alpha, c.beta) for c in fg]
     assert harness.cases_for(12)[0].name == tg[0].name and harness.cases_for(13)[-1].name == fg[-1].name
+
+
+def test_second_sweeps_repeat_the_recipes_of_the_first_from_streams_of_their_own():
+    first, second = wl.config4(), wl.config_sweep2()
+    assert (len(first), len(second)) == (2000, 4000)
+    assert all(1 <= min(c.M, c.N, c.K) and max(c.M, c.N, c.K) <= 8192 and 2 * c.M * c.N * c.K <= 2 ** 32 for c in second)
+    key = lambda c: (c.M, c.N, c.K, c.transA, c.transB)
+    assert len({key(c) for c in second} & {key(c) for c in first}) < 40  # another stream: only tiny shapes coincide
+    assert second[0].name.startswith("sweep2/") and first[0].name.startswith("cfg4/")
+    assert [key(c) for c in wl.config_sweep2()] == [key(c) for c in second]
+    thin2, flat2 = wl.config_thin2(), wl.config_flat2()
+    assert len(thin2) == 2000 and len(flat2) == 2000
+    assert all(1 <= c.N <= 64 and 256 <= c.M <= 16384 and 256 <= c.K <= 8192 for c in thin2)
+    assert all(16 <= c.M <= 512 and 1024 <= c.N <= 65536 and 16 <= c.K <= 4096 for c in flat2)
+    assert [key(c) for c in thin2[:100]] != [key(c) for c in wl.config_thin()[:100]]
+    assert harness.cases_for(14)[0].name == second[0].name and harness.cases_for(16)[-1].name == flat2[-1].name
