@@ -221,6 +221,11 @@ def config_sweep2(n_shapes=4000):
     return config4(n_shapes, config_index=14, prefix="sweep2")
 
 
+def config_sweep3(n_shapes=8000):
+    """A third random sweep of the same recipe, again from a stream of its own; all of it trains."""
+    return config4(n_shapes, config_index=17, prefix="sweep3")
+
+
 def fresh_shapes(n_shapes, seed_index=0, log2_max_dim=13.0, max_flops=2 ** 32, min_work=0):
     """[n, 5] int64 rows (M, N, K, tA, tB) drawn like the random sweep (dimensions round(2**(log2_max_dim * u)),
     the triple redrawn while 2 M N K > max_flops or M N K < min_work, fair-coin transposes), from a stream of its
@@ -346,6 +351,16 @@ def config_thin2(n_shapes=2000):
 def config_flat2(n_shapes=2000):
     """More of the flat corner, drawn like config_flat from a stream of its own."""
     return _log_uniform_sweep(16, "flat2", n_shapes, (16, 512), (1024, 65536), (16, 4096))
+
+
+def config_thin3(n_shapes=2000):
+    """A third draw of the thin corner."""
+    return _log_uniform_sweep(18, "thin3", n_shapes, (256, 16384), (1, 64), (256, 8192))
+
+
+def config_flat3(n_shapes=2000):
+    """A third draw of the flat corner."""
+    return _log_uniform_sweep(19, "flat3", n_shapes, (16, 512), (1024, 65536), (16, 4096))
 
 
 def _geometric_grid(lo, hi):
