@@ -48,6 +48,8 @@ the plain-Python oracle and the generated C++ agree bit for bit.
 from fractions import Fraction
 import math
 
+import sys
+
 import numpy as np
 
 RAW_FEATURES = ("M", "N", "K", "tA", "tB")
@@ -283,7 +285,12 @@ def fit_cart(X, times, H=None, L=1, leaf_rule="majority", fallback=0, labels=Non
         tree.right[node] = grow(idx[~go_left], depth + 1)
         return node
 
-    grow(np.arange(X.shape[0]), 0)
+    limit = sys.getrecursionlimit()
+    sys.setrecursionlimit(max(limit, 20000))  # one Python frame per tree level; unbalanced trees run hundreds deep
+    try:
+        grow(np.arange(X.shape[0]), 0)
+    finally:
+        sys.setrecursionlimit(limit)
     return tree
 
 

@@ -124,6 +124,9 @@ def main(argv=None):
                     help="host nanoseconds per evaluation of the single tree (if-then-else), fresh shapes")
     ap.add_argument("--forest-ns", type=float, default=490.0,
                     help="host nanoseconds per evaluation of the forest (table walk), fresh shapes")
+    ap.add_argument("--leaf-rules", nargs="*", default=["majority", "logratio", "regret"],
+                    help="leaf rules to sweep (the cost-sensitive splits of `regret` grow chain-like trees for L = 1 on "
+                         "tens of thousands of inputs and take hours; leave it out there)")
     ap.add_argument("--no-write", action="store_true")
     args = ap.parse_args(argv)
 
@@ -147,7 +150,7 @@ def main(argv=None):
     links = fallback_links(meta)  # what the dispatch does with an illegal prediction
 
     report = []
-    for rule in ("majority", "logratio", "regret"):
+    for rule in args.leaf_rules:
         rows = cart.sweep(Xtr, Ttr, Xte, Tte, leaf_rule=rule, fallback=links)
         print(f"\nleaf rule: {rule}\n{'model':12s} {'acc%':>6s} {'DTPR':>6s} {'geomean':>8s} {'leaves':>6s} {'height':>6s} {'classes':>7s}")
         for r in rows:

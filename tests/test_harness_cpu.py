@@ -120,3 +120,9 @@ def test_second_sweeps_repeat_the_recipes_of_the_first_from_streams_of_their_own
     assert all(16 <= c.M <= 512 and 1024 <= c.N <= 65536 and 16 <= c.K <= 4096 for c in flat2)
     assert [key(c) for c in thin2[:100]] != [key(c) for c in wl.config_thin()[:100]]
     assert harness.cases_for(14)[0].name == second[0].name and harness.cases_for(16)[-1].name == flat2[-1].name
+    third = wl.config_sweep3()
+    assert len(third) == 8000 and third[0].name.startswith("sweep3/")
+    assert len({key(c) for c in third} & {key(c) for c in second}) < 80
+    assert len(wl.config_thin3()) == 2000 and len(wl.config_flat3()) == 2000
+    assert [key(c) for c in wl.config_thin3()[:100]] != [key(c) for c in thin2[:100]]
+    assert harness.cases_for(17)[-1].name == third[-1].name and harness.cases_for(19)[0].name == wl.config_flat3()[0].name
