@@ -21,7 +21,7 @@ from . import cart
 from .train import RESULTS, load_table, split, training_union
 
 FRACTIONS = (1.0, 0.5, 0.25, 0.125, 0.0625, 0.03125, 0.015625)
-EXTRA = ("go2", "wide", "po2", "big", "large", "thin", "flat", "tgrid", "fgrid", "sweep2", "thin2", "flat2", "sweep3", "thin3", "flat3")  # the order train.py joins them in
+EXTRA = ("go2", "wide", "po2", "big", "large", "thin", "flat", "tgrid", "fgrid", "sweep2", "thin2", "flat2", "sweep3", "thin3", "flat3", "tgrid2")  # the order train.py joins them in
 
 
 def _load(name):

@@ -33,7 +33,7 @@ def main(folds=5):
         if t is not None:
             tests[key] = (t["X"], t["T"])
             excl.append(t)
-    extras = {n: _load(n) for n in ("go2", "po2", "wide", "big", "large", "thin", "flat", "tgrid", "fgrid", "sweep2", "thin2", "flat2", "sweep3", "thin3", "flat3")}
+    extras = {n: _load(n) for n in ("go2", "po2", "wide", "big", "large", "thin", "flat", "tgrid", "fgrid", "sweep2", "thin2", "flat2", "sweep3", "thin3", "flat3", "tgrid2")}
     extras = {n: t for n, t in extras.items() if t is not None}
     banned = set()
     for t in excl:

@@ -224,13 +224,15 @@ def cases_for(config):
         return [c.resolved() for c in wl.config_thin3()]
     if config == 19:
         return [c.resolved() for c in wl.config_flat3()]
+    if config == 20:
+        return [c.resolved() for c in wl.config_thin_grid2()]
     raise ValueError(config)
 
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--config", type=int, default=4,
-                    help="0-4: the five workload configurations; 5: go2 grid; 6: po2 grid; 7: wide random sweep; 8: large products; 9: coarse grid of the largest sizes; 10: thin (few columns); 11: flat (few rows); 12 / 13: geometric grids over the thin / flat corners; 14 / 17: second and third random sweep; 15, 18 / 16, 19: more thin / flat shapes")
+                    help="0-4: the five workload configurations; 5: go2 grid; 6: po2 grid; 7: wide random sweep; 8: large products; 9: coarse grid of the largest sizes; 10: thin (few columns); 11: flat (few rows); 12 / 13: geometric grids over the thin / flat corners; 14 / 17: second and third random sweep; 15, 18 / 16, 19: more thin / flat shapes; 20: denser grid over the thin corner")
     ap.add_argument("--out", default=None, help="the table to write (required unless --verify-every)")
     ap.add_argument("--start", type=int, default=0)
     ap.add_argument("--limit", type=int, default=10 ** 9)

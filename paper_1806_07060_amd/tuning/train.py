@@ -112,7 +112,7 @@ def main(argv=None):
     ap.add_argument("--extra", nargs="*", default=["timings_go2.csv", "timings_wide.csv", "timings_po2.csv", "timings_big.csv", "timings_large.csv",
                                                       "timings_thin.csv", "timings_flat.csv", "timings_tgrid.csv", "timings_fgrid.csv",
                                                       "timings_sweep2.csv", "timings_thin2.csv", "timings_flat2.csv",
-                                                      "timings_sweep3.csv", "timings_thin3.csv", "timings_flat3.csv"],
+                                                      "timings_sweep3.csv", "timings_thin3.csv", "timings_flat3.csv", "timings_tgrid2.csv"],
                     help="further tables (file names under results/) whose inputs join the training set")
     ap.add_argument("--exclude", nargs="*", default=["timings_cfg1.csv", "timings_cfg2.csv", "timings_cfg3.csv"],
                     help="tables whose shapes must stay out of the training set")

@@ -385,6 +385,17 @@ def config_thin_grid(max_flops=2 ** 38, max_operand_bytes=6e8):
     return _dress(triples, 12, "tgrid")
 
 
+def config_thin_grid2(max_flops=2 ** 38, max_operand_bytes=6e8):
+    """A denser grid over the thin corner: N also at the midpoints (3, 6, 12, ...), M in quarter octaves from 512
+    to 16384, K in half octaves from 512 to 8192; the triples config_thin_grid already holds are left out."""
+    ns = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128]
+    ms = sorted({(2 ** e) * q // 4 for e in range(9, 14) for q in (4, 5, 6, 7)} | {16384})
+    have = {(c.M, c.N, c.K) for c in config_thin_grid(max_flops, max_operand_bytes)}
+    triples = [(m, n, k) for m in ms for n in ns for k in _geometric_grid(512, 8192)
+               if (m, n, k) not in have and 2 * m * n * k <= max_flops and 4 * max(m * k, k * n, m * n) <= max_operand_bytes]
+    return _dress(triples, 20, "tgrid2")
+
+
 def config_flat_grid(max_flops=2 ** 38, max_operand_bytes=6e8):
     """Sparse geometric grid over the flat corner (few rows, very many columns: convolutions lowered to GEMM):
     M a power of two from 16 to 512, N and K powers of two and their midpoints."""

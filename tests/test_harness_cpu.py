@@ -126,3 +126,8 @@ def test_second_sweeps_repeat_the_recipes_of_the_first_from_streams_of_their_own
     assert len(wl.config_thin3()) == 2000 and len(wl.config_flat3()) == 2000
     assert [key(c) for c in wl.config_thin3()[:100]] != [key(c) for c in thin2[:100]]
     assert harness.cases_for(17)[-1].name == third[-1].name and harness.cases_for(19)[0].name == wl.config_flat3()[0].name
+    # the denser thin grid adds midpoints of N and quarter octaves of M, and repeats nothing of the first grid
+    tg, tg2 = wl.config_thin_grid(), wl.config_thin_grid2()
+    assert len(tg2) == 1854 and not {(c.M, c.N, c.K) for c in tg2} & {(c.M, c.N, c.K) for c in tg}
+    assert {3, 6, 12, 24, 48, 96} <= {c.N for c in tg2} and {640, 896, 7168, 14336} <= {c.M for c in tg2}
+    assert max(c.M for c in tg2) == 16384 and harness.cases_for(20)[0].name == tg2[0].name
